@@ -1,0 +1,393 @@
+/*
+ * CPU oracle for the SVG2 per-layer sparse-attention path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision implementation of what the path computes,
+ * written from the paper's definitions, one head at a time.  It shares no code
+ * with the HIP library and must never be called from the product path: only
+ * tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ *   dense attention            Section 3.1 (O = softmax(Q K^T / sqrt(d)) V)
+ *   k-means (Lloyd)            Section 4.1 (independent per head, Q and K)
+ *   permutation                Section 4.1 (pi_q, pi_k make clusters contiguous)
+ *   centroid scores + top-p    Section 4.2, Eq. 1 and Eq. 2, top-p rule
+ *   block-sparse attention     Section 4.3 with the equivalence of Section 4.1
+ *   density                    Section 5.1 "Metrics"
+ *
+ * Inputs are float arrays (bf16 workloads pass bf16-representable floats, so
+ * reading them is exact); every sum is accumulated in double.  OpenMP is used
+ * only over independent rows / tokens; there is no blocking or fusion.
+ *
+ * Readings of the paper where it is silent (kept in step with the HIP path's
+ * header): squared Euclidean distance, one iteration = assign then update,
+ * empty cluster keeps its centroid, argmin ties go to the lowest index, stable
+ * order inside a cluster, top-p keeps the element that crosses p, ties in P'
+ * go to the lower index, zero-size key clusters are never selected, softmax is
+ * renormalised over the selected keys only.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- bfloat16 rounding of a double (round to nearest, ties to even) ---- */
+static double round_bf16(double v)
+{
+    if (v == 0.0 || !isfinite(v)) return v;
+    int e;
+    double m = frexp(v, &e);            /* v = m * 2^e, 0.5 <= |m| < 1 */
+    /* bf16 keeps 8 significant bits: scale so that one ulp is 1.0 */
+    double scaled = ldexp(m, 8);        /* 128 <= |scaled| < 256 */
+    double r = nearbyint(scaled);       /* default rounding mode: ties to even */
+    return ldexp(r, e - 8);
+}
+
+/* ------------------------------------------------------------------------
+ * Dense attention, Section 3.1.  Q [Nq,d], K [Nk,d], V [Nk,d] -> O [Nq,d],
+ * lse [Nq] (natural-log sum of exp of the scaled scores), either may be NULL.
+ * ------------------------------------------------------------------------ */
+void svg2o_dense_attention(const float *Q, const float *K, const float *V,
+                           int Nq, int Nk, int d, double scale,
+                           double *O, double *lse)
+{
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(Nk > 0 ? Nk : 1));
+#pragma omp for schedule(dynamic, 16)
+        for (int n = 0; n < Nq; ++n) {
+            const float *q = Q + (size_t)n * d;
+            double mx = -INFINITY;
+            for (int m = 0; m < Nk; ++m) {
+                const float *k = K + (size_t)m * d;
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += (double)q[c] * (double)k[c];
+                s[m] = acc * scale;
+                if (s[m] > mx) mx = s[m];
+            }
+            double den = 0.0;
+            for (int m = 0; m < Nk; ++m) { s[m] = exp(s[m] - mx); den += s[m]; }
+            if (O) {
+                double *o = O + (size_t)n * d;
+                for (int c = 0; c < d; ++c) o[c] = 0.0;
+                for (int m = 0; m < Nk; ++m) {
+                    const float *v = V + (size_t)m * d;
+                    double p = s[m] / den;
+                    for (int c = 0; c < d; ++c) o[c] += p * (double)v[c];
+                }
+            }
+            if (lse) lse[n] = (Nk > 0) ? mx + log(den) : -INFINITY;
+        }
+        free(s);
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * k-means, Section 4.1.  X [N,d]; init [C,d]; T >= 1 iterations of
+ * (assign, update).  round_bf16_centroids != 0: the assign step sees the
+ * centroids rounded to bfloat16 (the storage type of X), the update step and
+ * the returned centroids stay unrounded means.
+ * Outputs: centroids [C,d] (means of the returned labels; an empty cluster
+ * keeps its previous centroid), labels [N], counts [C], and if non-NULL
+ * objective [2*T]: objective[2t] = sum of squared distances right after
+ * assign t (to the centroids that assign used), objective[2t+1] = the same
+ * sum right after update t (to the new means).
+ * ------------------------------------------------------------------------ */
+void svg2o_kmeans(const float *X, int N, int d, int C, int T,
+                  int round_bf16_centroids, const double *init,
+                  double *centroids, int32_t *labels, int32_t *counts,
+                  double *objective)
+{
+    double *c = centroids;
+    if (c != init) memcpy(c, init, sizeof(double) * (size_t)C * d);
+    double *cr = (double *)malloc(sizeof(double) * (size_t)C * d);
+    double *cn = (double *)malloc(sizeof(double) * (size_t)C);
+    double *sum = (double *)malloc(sizeof(double) * (size_t)C * d);
+
+    for (int t = 0; t < T; ++t) {
+        /* centroids as the assign step sees them, and their squared norms */
+        for (size_t i = 0; i < (size_t)C * d; ++i)
+            cr[i] = round_bf16_centroids ? round_bf16(c[i]) : c[i];
+        for (int j = 0; j < C; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < d; ++k) a += cr[(size_t)j * d + k] * cr[(size_t)j * d + k];
+            cn[j] = a;
+        }
+        /* assign: argmin_j ||c_j||^2 - 2 x.c_j  (||x||^2 is common to all j) */
+        double J = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : J)
+        for (int n = 0; n < N; ++n) {
+            const float *x = X + (size_t)n * d;
+            double best = INFINITY;
+            int bj = 0;
+            for (int j = 0; j < C; ++j) {
+                const double *cj = cr + (size_t)j * d;
+                double dot = 0.0;
+                for (int k = 0; k < d; ++k) dot += (double)x[k] * cj[k];
+                double dist = cn[j] - 2.0 * dot;
+                if (dist < best) { best = dist; bj = j; }
+            }
+            labels[n] = bj;
+            double xx = 0.0;
+            for (int k = 0; k < d; ++k) xx += (double)x[k] * (double)x[k];
+            J += xx + best;
+        }
+        if (objective) objective[2 * t] = J;
+
+        /* update: mean of each cluster's members, in token order */
+        memset(sum, 0, sizeof(double) * (size_t)C * d);
+        memset(counts, 0, sizeof(int32_t) * (size_t)C);
+        for (int n = 0; n < N; ++n) {
+            const float *x = X + (size_t)n * d;
+            double *s = sum + (size_t)labels[n] * d;
+            for (int k = 0; k < d; ++k) s[k] += (double)x[k];
+            counts[labels[n]] += 1;
+        }
+        for (int j = 0; j < C; ++j) {
+            if (counts[j] == 0) continue;            /* empty: keep previous centroid */
+            for (int k = 0; k < d; ++k)
+                c[(size_t)j * d + k] = sum[(size_t)j * d + k] / (double)counts[j];
+        }
+        if (objective) {
+            double J2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : J2)
+            for (int n = 0; n < N; ++n) {
+                const float *x = X + (size_t)n * d;
+                const double *cj = c + (size_t)labels[n] * d;
+                double a = 0.0;
+                for (int k = 0; k < d; ++k) { double e = (double)x[k] - cj[k]; a += e * e; }
+                J2 += a;
+            }
+            objective[2 * t + 1] = J2;
+        }
+    }
+    free(cr); free(cn); free(sum);
+}
+
+/* Relative gap between the two smallest full squared distances of each token
+ * to the given centroids (as the assign step would see them): used by tests to
+ * decide whether a label disagreement is a near-tie.  gap [N]. */
+void svg2o_top2_gap(const float *X, int N, int d, int C, int round_bf16_centroids,
+                    const double *centroids, double *gap)
+{
+    double *cr = (double *)malloc(sizeof(double) * (size_t)C * d);
+    for (size_t i = 0; i < (size_t)C * d; ++i)
+        cr[i] = round_bf16_centroids ? round_bf16(centroids[i]) : centroids[i];
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const float *x = X + (size_t)n * d;
+        double d1 = INFINITY, d2 = INFINITY;
+        for (int j = 0; j < C; ++j) {
+            const double *cj = cr + (size_t)j * d;
+            double a = 0.0;
+            for (int k = 0; k < d; ++k) { double e = (double)x[k] - cj[k]; a += e * e; }
+            if (a < d1) { d2 = d1; d1 = a; } else if (a < d2) { d2 = a; }
+        }
+        gap[n] = (C > 1) ? (d2 - d1) / fmax(fabs(d2), 1e-12) : INFINITY;
+    }
+    free(cr);
+}
+
+/* ------------------------------------------------------------------------
+ * Permutation, Section 4.1.  labels [N] in [0,C) -> counts [C], offsets [C+1]
+ * (exclusive scan), perm [N] (sorted position r holds original token perm[r];
+ * clusters ascending, original order kept inside a cluster), inv_perm [N].
+ * ------------------------------------------------------------------------ */
+void svg2o_permute(const int32_t *labels, int N, int C,
+                   int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm)
+{
+    memset(counts, 0, sizeof(int32_t) * (size_t)C);
+    for (int n = 0; n < N; ++n) counts[labels[n]] += 1;
+    offsets[0] = 0;
+    for (int j = 0; j < C; ++j) offsets[j + 1] = offsets[j] + counts[j];
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)(C > 0 ? C : 1));
+    memcpy(cursor, offsets, sizeof(int32_t) * (size_t)C);
+    for (int n = 0; n < N; ++n) {
+        int r = cursor[labels[n]]++;
+        perm[r] = n;
+        if (inv_perm) inv_perm[n] = r;
+    }
+    free(cursor);
+}
+
+/* X' [r] = X [perm[r]] : the product pi X of Section 4.1 for a row-index permutation. */
+void svg2o_gather_rows(const float *X, const int32_t *perm, int N, int d, float *Xp)
+{
+    for (int r = 0; r < N; ++r)
+        memcpy(Xp + (size_t)r * d, X + (size_t)perm[r] * d, sizeof(float) * (size_t)d);
+}
+
+/* ------------------------------------------------------------------------
+ * Centroid scores and top-p selection, Section 4.2.
+ *   S_ij  = cq_i . ck_j / sqrt(d)                                   (Eq. 1)
+ *   P'_ij = |K_j| exp(S_ij) / sum_k |K_k| exp(S_ik)                 (Eq. 2)
+ * For every query cluster i: key clusters in descending P' (ties: lower j
+ * first); the element at sorted position t is kept iff the sum of the
+ * elements before it is < p, so the one that crosses p is included.  p >= 1
+ * keeps every non-empty key cluster.  Key clusters of size 0 are never kept;
+ * a query cluster of size 0 (when counts_q is given) gets an empty row.
+ * Outputs: row_ptr [Cq+1], col_idx [capacity Cq*Ck] ascending inside a row,
+ * p_est [Cq,Ck] or NULL, margin [Cq] or NULL (how far the stopping decision
+ * of the row is from flipping: min of |sum before last kept - p|, |sum
+ * including last kept - p| and the P' gap between last kept and first
+ * dropped), density (Section 5.1; needs counts_q, else NaN).
+ * ------------------------------------------------------------------------ */
+typedef struct { double p; int j; } svg2o_pj;
+
+static int cmp_desc(const void *a, const void *b)
+{
+    const svg2o_pj *x = (const svg2o_pj *)a, *y = (const svg2o_pj *)b;
+    if (x->p > y->p) return -1;
+    if (x->p < y->p) return 1;
+    return (x->j > y->j) - (x->j < y->j);
+}
+
+void svg2o_select_topp(const double *cq, const double *ck,
+                       const int32_t *counts_q, const int32_t *counts_k,
+                       int Cq, int Ck, int d, double top_p,
+                       int32_t *row_ptr, int32_t *col_idx,
+                       double *p_est, double *margin, double *density)
+{
+    double *P = (double *)malloc(sizeof(double) * (size_t)Ck);
+    svg2o_pj *ord = (svg2o_pj *)malloc(sizeof(svg2o_pj) * (size_t)Ck);
+    char *keep = (char *)malloc((size_t)Ck);
+    double inv_sqrt_d = 1.0 / sqrt((double)d);
+    long long nq_total = 0, nk_total = 0;
+    double work = 0.0;
+    for (int j = 0; j < Ck; ++j) nk_total += counts_k[j];
+    row_ptr[0] = 0;
+    for (int i = 0; i < Cq; ++i) {
+        /* Eq. 1 */
+        double mx = -INFINITY;
+        for (int j = 0; j < Ck; ++j) {
+            double a = 0.0;
+            for (int k = 0; k < d; ++k) a += cq[(size_t)i * d + k] * ck[(size_t)j * d + k];
+            P[j] = a * inv_sqrt_d;
+            if (counts_k[j] > 0 && P[j] > mx) mx = P[j];
+        }
+        /* Eq. 2, with the row maximum subtracted from S (cancels in the ratio) */
+        double den = 0.0;
+        for (int j = 0; j < Ck; ++j) {
+            P[j] = (counts_k[j] > 0) ? (double)counts_k[j] * exp(P[j] - mx) : 0.0;
+            den += P[j];
+        }
+        for (int j = 0; j < Ck; ++j) {
+            P[j] = (den > 0.0) ? P[j] / den : 0.0;
+            if (p_est) p_est[(size_t)i * Ck + j] = P[j];
+        }
+        /* top-p */
+        memset(keep, 0, (size_t)Ck);
+        double mg = INFINITY;
+        int empty_row = (counts_q && counts_q[i] == 0);
+        if (!empty_row) {
+            if (top_p >= 1.0) {
+                for (int j = 0; j < Ck; ++j) keep[j] = counts_k[j] > 0;
+            } else {
+                for (int j = 0; j < Ck; ++j) { ord[j].p = P[j]; ord[j].j = j; }
+                qsort(ord, (size_t)Ck, sizeof(svg2o_pj), cmp_desc);
+                double cum = 0.0, last = 0.0, first_dropped = -1.0;
+                int n_kept = 0;
+                for (int t = 0; t < Ck; ++t) {
+                    int j = ord[t].j;
+                    if (counts_k[j] == 0) continue;          /* never kept */
+                    if (!(cum < top_p)) { first_dropped = ord[t].p; break; }
+                    keep[j] = 1;
+                    last = ord[t].p;
+                    cum += last;
+                    n_kept += 1;
+                }
+                if (n_kept > 0) {
+                    double before = cum - last;
+                    mg = fmin(fabs(before - top_p), fabs(cum - top_p));
+                    if (first_dropped >= 0.0) mg = fmin(mg, last - first_dropped);
+                }
+            }
+        }
+        if (margin) margin[i] = mg;
+        int nnz = row_ptr[i];
+        long long keys = 0;
+        for (int j = 0; j < Ck; ++j)
+            if (keep[j]) { col_idx[nnz++] = j; keys += counts_k[j]; }
+        row_ptr[i + 1] = nnz;
+        if (counts_q) { nq_total += counts_q[i]; work += (double)counts_q[i] * (double)keys; }
+    }
+    if (density)
+        *density = (counts_q && nq_total > 0 && nk_total > 0)
+                       ? work / ((double)nq_total * (double)nk_total) : NAN;
+    free(P); free(ord); free(keep);
+}
+
+/* ------------------------------------------------------------------------
+ * Block-sparse attention over variable-size clusters, Section 4.3.
+ * Qp, Kp, Vp are the permuted tensors (clusters contiguous; cluster i of Q is
+ * rows offsets_q[i]..offsets_q[i+1]).  Every row of query cluster i attends,
+ * with an ordinary softmax, over exactly the keys of its selected key
+ * clusters.  perm_q != NULL: the result of permuted row r is written to
+ * original row perm_q[r] (pi_q^T of Section 4.1); else it stays at r.
+ * rows != NULL: only the n_rows permuted rows listed are computed (the rest
+ * of O is left untouched) -- rows are independent, so a sample is exact.
+ * A row with no selected key gets O = 0, lse = -inf.
+ * ------------------------------------------------------------------------ */
+void svg2o_sparse_attention(const float *Qp, const float *Kp, const float *Vp,
+                            int N, int d, int Cq, int Ck,
+                            const int32_t *offsets_q, const int32_t *offsets_k,
+                            const int32_t *row_ptr, const int32_t *col_idx,
+                            const int32_t *perm_q, double scale,
+                            const int32_t *rows, int n_rows,
+                            double *O, double *lse)
+{
+    (void)Ck;
+    int total = rows ? n_rows : N;
+    /* cluster of every permuted query row */
+    int32_t *cl = (int32_t *)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    for (int i = 0; i < Cq; ++i)
+        for (int r = offsets_q[i]; r < offsets_q[i + 1]; ++r) cl[r] = i;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double *acc = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 8)
+        for (int t = 0; t < total; ++t) {
+            int r = rows ? rows[t] : t;
+            int i = cl[r];
+            const float *q = Qp + (size_t)r * d;
+            int cnt = 0;
+            double mx = -INFINITY;
+            for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                int j = col_idx[e];
+                for (int m = offsets_k[j]; m < offsets_k[j + 1]; ++m) {
+                    const float *k = Kp + (size_t)m * d;
+                    double a = 0.0;
+                    for (int c = 0; c < d; ++c) a += (double)q[c] * (double)k[c];
+                    a *= scale;
+                    s[cnt++] = a;
+                    if (a > mx) mx = a;
+                }
+            }
+            double den = 0.0;
+            for (int u = 0; u < cnt; ++u) { s[u] = exp(s[u] - mx); den += s[u]; }
+            for (int c = 0; c < d; ++c) acc[c] = 0.0;
+            cnt = 0;
+            for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                int j = col_idx[e];
+                for (int m = offsets_k[j]; m < offsets_k[j + 1]; ++m) {
+                    const float *v = Vp + (size_t)m * d;
+                    double p = s[cnt++] / den;
+                    for (int c = 0; c < d; ++c) acc[c] += p * (double)v[c];
+                }
+            }
+            size_t dst = (size_t)(perm_q ? perm_q[r] : r);
+            if (O) for (int c = 0; c < d; ++c) O[dst * d + c] = (cnt > 0) ? acc[c] : 0.0;
+            if (lse) lse[dst] = (cnt > 0) ? mx + log(den) : -INFINITY;
+        }
+        free(s); free(acc);
+    }
+    free(cl);
+}
+
+/* Accounting helper for the paper's padding example (Section 4.3): the share
+ * of a fixed bm x bn tile that is padding when it holds a rows x cols block. */
+double svg2o_padding_waste(int rows, int cols, int bm, int bn)
+{
+    long long tiles_r = (rows + bm - 1) / bm, tiles_c = (cols + bn - 1) / bn;
+    double padded = (double)(tiles_r * bm) * (double)(tiles_c * bn);
+    return padded > 0.0 ? 1.0 - ((double)rows * (double)cols) / padded : 0.0;
+}

@@ -1,0 +1,404 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- library routines (torch SDPA, scipy softmax / kmeans2,
+scikit-learn Lloyd, numpy stable argsort), closed forms, invariants the paper
+proves (Section 4.1 permutation equivalence), brute force on tiny inputs and
+the one worked number the paper prints (Section 4.3 padding example)."""
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _sdpa(Q, K, V, scale=None):
+    """Library dense attention in float64."""
+    q, k, v = (torch.from_numpy(np.asarray(a, dtype=np.float64))[None, None] for a in (Q, K, V))
+    o = torch.nn.functional.scaled_dot_product_attention(q, k, v, scale=scale)
+    return o[0, 0].numpy()
+
+
+# ------------------------------------------------------------------ dense attention (Section 3.1)
+
+def test_dense_matches_library_sdpa(oracle):
+    r = _rng(0)
+    Q, K, V = r.standard_normal((37, 24)), r.standard_normal((53, 24)), r.standard_normal((53, 24))
+    O, lse = oracle.dense_attention(Q, K, V)
+    np.testing.assert_allclose(O, _sdpa(Q.astype(np.float32), K.astype(np.float32), V.astype(np.float32)),
+                               rtol=1e-10, atol=1e-12)
+    S = (Q.astype(np.float32).astype(np.float64) @ K.astype(np.float32).astype(np.float64).T) / np.sqrt(24)
+    np.testing.assert_allclose(lse, scipy.special.logsumexp(S, axis=1), rtol=1e-12)
+
+
+def test_dense_closed_forms(oracle):
+    r = _rng(1)
+    Q, K = r.standard_normal((9, 8)), r.standard_normal((11, 8))
+    # constant V -> constant output
+    V = np.tile(r.standard_normal((1, 8)), (11, 1))
+    O, _ = oracle.dense_attention(Q, K, V)
+    np.testing.assert_allclose(O, np.tile(V[:1].astype(np.float32), (9, 1)), rtol=1e-12)
+    # a single key -> its value row, lse = the score
+    V1 = r.standard_normal((1, 8))
+    O, lse = oracle.dense_attention(Q, K[:1], V1)
+    np.testing.assert_allclose(O, np.tile(V1.astype(np.float32), (9, 1)), rtol=1e-12)
+    s = (Q.astype(np.float32).astype(np.float64) @ K[:1].astype(np.float32).astype(np.float64).T)[:, 0] / np.sqrt(8)
+    np.testing.assert_allclose(lse, s, rtol=1e-12)
+    # zero queries -> uniform weights: O = mean(V), lse = log Nk
+    V = r.standard_normal((11, 8))
+    O, lse = oracle.dense_attention(np.zeros((3, 8)), K, V)
+    np.testing.assert_allclose(O, np.tile(V.astype(np.float32).astype(np.float64).mean(0), (3, 1)), rtol=1e-12)
+    np.testing.assert_allclose(lse, np.log(11.0), rtol=1e-12)
+    # two keys -> logistic function of the score difference, scale applied once
+    q = np.array([[2.0, 0.0]]); K2 = np.array([[1.0, 0.0], [-1.0, 0.0]]); V2 = np.array([[1.0, 0.0], [0.0, 1.0]])
+    O, _ = oracle.dense_attention(q, K2, V2)
+    w = 1.0 / (1.0 + np.exp(-(4.0 / np.sqrt(2.0))))
+    np.testing.assert_allclose(O, [[w, 1.0 - w]], rtol=1e-12)
+
+
+def test_dense_rectangular_uses_value_of_matching_key(oracle):
+    # catches a transposed operand: one-hot-like scores pick distinct value rows
+    K = np.eye(4) * 50.0
+    Q = np.eye(4)[[2, 0, 3]] * 50.0
+    V = np.arange(16, dtype=np.float64).reshape(4, 4)
+    O, _ = oracle.dense_attention(Q, K, V)
+    np.testing.assert_allclose(O, V[[2, 0, 3]], atol=1e-9)
+
+
+# ------------------------------------------------------------------ k-means (Section 4.1)
+
+def _mixture(r, N, d, M, sep):
+    mu = sep * r.standard_normal((M, d))
+    comp = r.integers(0, M, size=N)
+    X = (mu[comp] + r.standard_normal((N, d))).astype(np.float32)
+    return X, mu, comp
+
+
+def test_kmeans_matches_scipy_kmeans2(oracle):
+    from scipy.cluster.vq import kmeans2
+    r = _rng(2)
+    X, _, _ = _mixture(r, 600, 8, 5, 1.0)
+    init = X[r.choice(600, 12, replace=False)].astype(np.float64)
+    for T in (1, 2, 5):
+        res = oracle.kmeans(X, init, T, round_bf16=False)
+        cb, lab = kmeans2(X.astype(np.float64), init.copy(), iter=T, minit="matrix", missing="warn")
+        np.testing.assert_array_equal(res.labels, lab)
+        np.testing.assert_allclose(res.centroids, cb, rtol=1e-10, atol=1e-12)
+        np.testing.assert_array_equal(res.counts, np.bincount(lab, minlength=12))
+
+
+def test_kmeans_matches_sklearn_lloyd(oracle):
+    from sklearn.cluster import KMeans
+    r = _rng(3)
+    X, _, _ = _mixture(r, 500, 6, 4, 2.0)
+    init = X[r.choice(500, 7, replace=False)].astype(np.float64)
+    T = 3
+    res = oracle.kmeans(X, init, T, round_bf16=False)
+    assert res.counts.min() > 0          # scikit-learn relocates empty clusters; none here
+    km = KMeans(n_clusters=7, init=init, n_init=1, max_iter=T, tol=0.0, algorithm="lloyd").fit(X.astype(np.float64))
+    np.testing.assert_allclose(res.centroids, km.cluster_centers_, rtol=1e-6, atol=1e-8)
+
+
+def test_kmeans_objective_never_increases(oracle):
+    r = _rng(4)
+    X, _, _ = _mixture(r, 800, 16, 6, 0.7)
+    init = X[r.choice(800, 20, replace=False)]
+    res = oracle.kmeans(X, init, 8, round_bf16=False)
+    J = res.objective
+    assert np.all(np.diff(J) <= 1e-9 * J[0]), J
+    # the value itself: brute force against the returned means
+    d2 = ((X.astype(np.float64) - res.centroids[res.labels]) ** 2).sum()
+    np.testing.assert_allclose(J[-1], d2, rtol=1e-12)
+    # with centroids rounded for the assign step each half step still cannot increase
+    res = oracle.kmeans(X, init, 6, round_bf16=True)
+    J = res.objective
+    assert np.all(J[1::2] <= J[0::2] * (1 + 1e-12))     # update <= the assign before it
+
+
+def test_kmeans_special_cases(oracle):
+    r = _rng(5)
+    X = r.standard_normal((300, 5)).astype(np.float32)
+    # C = 1: the centroid is the global mean after one iteration
+    res = oracle.kmeans(X, np.zeros((1, 5)), 1, False)
+    np.testing.assert_allclose(res.centroids[0], X.astype(np.float64).mean(0), rtol=1e-12)
+    assert res.counts[0] == 300 and not res.labels.any()
+    # C = N with the points as centroids: identity labels, zero objective
+    res = oracle.kmeans(X[:40], X[:40], 2, False)
+    np.testing.assert_array_equal(res.labels, np.arange(40))
+    np.testing.assert_allclose(res.objective, 0.0, atol=1e-9)
+    # counts sum to N, centroid * count = sum of members
+    init = X[:9]
+    res = oracle.kmeans(X, init, 3, False)
+    assert res.counts.sum() == 300
+    for j in range(9):
+        np.testing.assert_allclose(res.centroids[j] * res.counts[j],
+                                   X[res.labels == j].astype(np.float64).sum(0), rtol=1e-10, atol=1e-10)
+
+
+def test_kmeans_recovers_separated_mixture_and_is_stable_under_warm_start(oracle):
+    r = _rng(6)
+    X, mu, comp = _mixture(r, 1000, 12, 6, 8.0)
+    res = oracle.kmeans(X, mu, 3, False)
+    np.testing.assert_array_equal(res.labels, comp)
+    again = oracle.kmeans(X, res.centroids, 2, False)
+    np.testing.assert_array_equal(again.labels, res.labels)
+    np.testing.assert_allclose(again.centroids, res.centroids, rtol=1e-12)
+
+
+def test_kmeans_tie_goes_to_lowest_index_and_empty_cluster_keeps_centroid(oracle):
+    X = np.array([[0.0, 0.0], [1.0, 0.0], [0.0, 1.0], [1.0, 1.0]], dtype=np.float32)
+    far = np.array([100.0, 100.0])
+    init = np.array([[0.5, 0.5], [0.5, 0.5], far])          # clusters 0 and 1 tie everywhere
+    res = oracle.kmeans(X, init, 2, False)
+    np.testing.assert_array_equal(res.labels, [0, 0, 0, 0])
+    np.testing.assert_array_equal(res.counts, [4, 0, 0])
+    np.testing.assert_allclose(res.centroids[1], [0.5, 0.5])
+    np.testing.assert_allclose(res.centroids[2], far)
+    # the sign of the cross term matters: the nearest centroid is NOT the one with the smallest norm
+    X = np.array([[10.0, 0.0]], dtype=np.float32)
+    res = oracle.kmeans(X, np.array([[0.0, 0.0], [9.0, 0.0]]), 1, False)
+    assert res.labels[0] == 1
+
+
+def test_kmeans_assign_sees_bf16_rounded_centroids(oracle):
+    r = _rng(7)
+    X = r.standard_normal((400, 16)).astype(np.float32)
+    X = torch.from_numpy(X).to(torch.bfloat16).to(torch.float32).numpy()
+    init = (X[:10] + 0.37 * r.standard_normal((10, 16))).astype(np.float32)
+    res = oracle.kmeans(X, init, 1, round_bf16=True)
+    cr = torch.from_numpy(init).to(torch.bfloat16).to(torch.float64).numpy()      # library rounding (RNE)
+    dist = ((X.astype(np.float64)[:, None, :] - cr[None]) ** 2).sum(-1)
+    np.testing.assert_array_equal(res.labels, dist.argmin(1))
+    # the returned centroids are unrounded means
+    for j in range(10):
+        if res.counts[j]:
+            np.testing.assert_allclose(res.centroids[j], X[res.labels == j].astype(np.float64).mean(0), rtol=1e-12)
+    # and the top-2 gap helper agrees with a sort of the same distances
+    gap = oracle.top2_gap(X, init, True)
+    ds = np.sort(dist, axis=1)
+    np.testing.assert_allclose(gap, (ds[:, 1] - ds[:, 0]) / ds[:, 1], rtol=1e-9, atol=1e-12)
+
+
+# ------------------------------------------------------------------ permutation (Section 4.1)
+
+def test_permute_is_a_stable_sort_by_label(oracle):
+    r = _rng(8)
+    labels = r.integers(0, 13, size=1000).astype(np.int32)
+    labels[labels == 5] = 6                                  # leave one cluster empty
+    res = oracle.permute(labels, 13)
+    np.testing.assert_array_equal(res.perm, np.argsort(labels, kind="stable"))
+    np.testing.assert_array_equal(res.counts, np.bincount(labels, minlength=13))
+    np.testing.assert_array_equal(res.offsets, np.concatenate([[0], np.cumsum(res.counts)]))
+    assert res.offsets[-1] == 1000 and res.counts[5] == 0
+    np.testing.assert_array_equal(np.sort(res.perm), np.arange(1000))        # bijection
+    np.testing.assert_array_equal(res.inv_perm[res.perm], np.arange(1000))   # inverse
+    np.testing.assert_array_equal(res.perm[res.inv_perm], np.arange(1000))
+    assert np.all(np.diff(labels[res.perm]) >= 0)
+    X = r.standard_normal((1000, 4)).astype(np.float32)
+    np.testing.assert_array_equal(oracle.gather_rows(X, res.perm), X[res.perm])
+
+
+# ------------------------------------------------------------------ Eq. 1, Eq. 2, top-p (Section 4.2)
+
+def test_select_hand_worked_example(oracle):
+    # zero centroids -> S = 0 -> P' is the size share: 0.1, 0.2, 0.3, 0.4
+    cq = np.zeros((2, 4)); ck = np.zeros((4, 4))
+    counts_k = np.array([1, 2, 3, 4])
+    res = oracle.select_topp(cq, ck, np.array([5, 7]), counts_k, 0.65)
+    np.testing.assert_allclose(res.p_est, np.tile([0.1, 0.2, 0.3, 0.4], (2, 1)), rtol=1e-12)
+    np.testing.assert_array_equal(res.row_ptr, [0, 2, 4])
+    np.testing.assert_array_equal(res.col_idx, [2, 3, 2, 3])                 # 0.4 + 0.3 crosses 0.65
+    np.testing.assert_allclose(res.density, 0.7, rtol=1e-12)                 # 7 of 10 keys for every query
+    np.testing.assert_allclose(res.margin, [0.05, 0.05], rtol=1e-9)
+    res = oracle.select_topp(cq, ck, None, counts_k, 0.75)
+    np.testing.assert_array_equal(res.col_idx, [1, 2, 3, 1, 2, 3])
+    res = oracle.select_topp(cq, ck, None, counts_k, 0.3)                    # first element alone suffices
+    np.testing.assert_array_equal(res.col_idx, [3, 3])
+    # a score that favours the small cluster: S = ln 8 for cluster 0 -> weights 8,2,3,4
+    ckb = np.zeros((4, 4)); ckb[0, 0] = 2.0 * np.log(8.0)
+    cqb = np.zeros((1, 4)); cqb[0, 0] = 1.0                                  # sqrt(d) = 2
+    res = oracle.select_topp(cqb, ckb, None, counts_k, 0.5)
+    np.testing.assert_allclose(res.p_est[0], np.array([8, 2, 3, 4]) / 17.0, rtol=1e-12)
+    np.testing.assert_array_equal(res.col_idx, [0, 3])
+
+
+def test_select_probabilities(oracle):
+    r = _rng(9)
+    cq, ck = r.standard_normal((7, 16)), r.standard_normal((19, 16))
+    counts = r.integers(1, 50, size=19)
+    res = oracle.select_topp(cq, ck, None, counts, 0.9)
+    np.testing.assert_allclose(res.p_est.sum(1), 1.0, rtol=1e-12)
+    S = cq @ ck.T / 4.0
+    # equal sizes -> plain softmax of S (library)
+    eq = oracle.select_topp(cq, ck, None, np.full(19, 3), 0.9)
+    np.testing.assert_allclose(eq.p_est, scipy.special.softmax(S, axis=1), rtol=1e-11)
+    # general sizes -> softmax of S + ln|K_j|
+    np.testing.assert_allclose(res.p_est, scipy.special.softmax(S + np.log(counts)[None], axis=1), rtol=1e-11)
+    # a cluster of size |K_j| weighs like |K_j| singleton clusters at the same centroid
+    rep = np.repeat(np.arange(19), counts)
+    single = oracle.select_topp(cq, ck[rep], None, np.ones(rep.size, dtype=np.int32), 0.9)
+    merged = np.zeros_like(res.p_est)
+    np.add.at(merged.T, rep, single.p_est.T)
+    np.testing.assert_allclose(res.p_est, merged, rtol=1e-10)
+    # huge logits do not overflow
+    big = oracle.select_topp(cq * 100, ck * 100, None, counts, 0.9)
+    assert np.isfinite(big.p_est).all()
+    np.testing.assert_allclose(big.p_est.sum(1), 1.0, rtol=1e-12)
+
+
+def test_select_singletons_reproduce_exact_attention_and_oracle_policy(oracle):
+    # every token its own cluster: P' is the true attention matrix and the
+    # selection is the oracle policy of Section 3.1 (rank keys by true score)
+    r = _rng(10)
+    Q, K = r.standard_normal((40, 8)), 1.5 * r.standard_normal((60, 8))
+    res = oracle.select_topp(Q, K, np.ones(40, dtype=np.int32), np.ones(60, dtype=np.int32), 0.8)
+    P = scipy.special.softmax(Q @ K.T / np.sqrt(8), axis=1)
+    np.testing.assert_allclose(res.p_est, P, rtol=1e-11)
+    for i in range(40):
+        order = np.argsort(-P[i], kind="stable")
+        cum = np.cumsum(P[i][order])
+        n_keep = int(np.searchsorted(cum, 0.8, side="left")) + 1            # first prefix with mass >= p
+        got = res.col_idx[res.row_ptr[i]:res.row_ptr[i + 1]]
+        np.testing.assert_array_equal(got, np.sort(order[:n_keep]))
+
+
+def test_select_minimal_prefix_monotone_and_p_one(oracle):
+    r = _rng(11)
+    cq, ck = 2 * r.standard_normal((12, 8)), 2 * r.standard_normal((30, 8))
+    counts = r.integers(0, 9, size=30)
+    counts[[3, 17]] = 0
+    prev = None
+    for p in (0.3, 0.5, 0.8, 0.9, 0.99, 1.0):
+        res = oracle.select_topp(cq, ck, None, counts, p)
+        rows = [set(res.col_idx[res.row_ptr[i]:res.row_ptr[i + 1]].tolist()) for i in range(12)]
+        for i, s in enumerate(rows):
+            assert len(s) >= 1 and 3 not in s and 17 not in s
+            cols = np.array(sorted(s))
+            np.testing.assert_array_equal(res.col_idx[res.row_ptr[i]:res.row_ptr[i + 1]], cols)   # ascending
+            mass = res.p_est[i, cols]
+            if p < 1.0:
+                assert mass.sum() >= p - 1e-12                        # reaches the target ...
+                assert mass.sum() - mass.min() < p                    # ... and no kept element is superfluous
+                assert mass.min() >= np.delete(res.p_est[i], cols).max(initial=0.0)   # kept = the largest
+            else:
+                assert s == set(np.nonzero(counts)[0].tolist())
+            if prev is not None:
+                assert prev[i] <= s                                    # monotone in p
+        prev = rows
+    # a query cluster of size 0 gets an empty row
+    cnt_q = np.ones(12, dtype=np.int32); cnt_q[4] = 0
+    res = oracle.select_topp(cq, ck, cnt_q, counts, 0.9)
+    assert res.row_ptr[5] == res.row_ptr[4]
+
+
+def test_select_ties_go_to_lower_index(oracle):
+    cq = np.zeros((1, 2)); ck = np.zeros((4, 2))
+    res = oracle.select_topp(cq, ck, None, np.array([2, 2, 2, 2]), 0.5)      # four equal 0.25
+    np.testing.assert_array_equal(res.col_idx, [0, 1])
+
+
+def test_density_counts_selected_pairs(oracle):
+    r = _rng(12)
+    cq, ck = r.standard_normal((5, 4)), r.standard_normal((8, 4))
+    cnt_q, cnt_k = r.integers(1, 20, size=5), r.integers(1, 20, size=8)
+    res = oracle.select_topp(cq, ck, cnt_q, cnt_k, 0.6)
+    mask = np.zeros((cnt_q.sum(), cnt_k.sum()), dtype=bool)                  # the token-level attention mask
+    oq, ok = np.concatenate([[0], np.cumsum(cnt_q)]), np.concatenate([[0], np.cumsum(cnt_k)])
+    for i in range(5):
+        for j in res.col_idx[res.row_ptr[i]:res.row_ptr[i + 1]]:
+            mask[oq[i]:oq[i + 1], ok[j]:ok[j + 1]] = True
+    np.testing.assert_allclose(res.density, mask.mean(), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ sparse attention (Sections 4.1, 4.3)
+
+def _random_partition(r, N, C):
+    labels = r.integers(0, C, size=N).astype(np.int32)
+    return labels
+
+
+def test_sparse_attention_with_everything_selected_is_dense_for_any_permutation(oracle):
+    # the equivalence proved in Section 4.1
+    r = _rng(13)
+    N, d, Cq, Ck = 150, 16, 7, 11
+    Q, K, V = (r.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    pq = oracle.permute(_random_partition(r, N, Cq), Cq)
+    pk = oracle.permute(_random_partition(r, N, Ck), Ck)
+    row_ptr = np.arange(Cq + 1, dtype=np.int32) * Ck
+    col_idx = np.tile(np.arange(Ck, dtype=np.int32), Cq)
+    O, lse = oracle.sparse_attention(Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets,
+                                     row_ptr, col_idx, perm_q=pq.perm)
+    np.testing.assert_allclose(O, _sdpa(Q, K, V), rtol=1e-10, atol=1e-12)
+    # without perm_q the rows stay in permuted order
+    O2, _ = oracle.sparse_attention(Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets, row_ptr, col_idx)
+    np.testing.assert_allclose(O2, _sdpa(Q, K, V)[pq.perm], rtol=1e-10, atol=1e-12)
+
+
+def test_sparse_attention_rows_equal_library_attention_over_selected_keys(oracle):
+    r = _rng(14)
+    N, d, Cq, Ck = 120, 8, 5, 9
+    Q, K, V = (r.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    lq, lk = _random_partition(r, N, Cq), _random_partition(r, N, Ck)
+    pq, pk = oracle.permute(lq, Cq), oracle.permute(lk, Ck)
+    sel = [np.sort(r.choice(Ck, size=r.integers(1, Ck), replace=False)) for _ in range(Cq)]
+    row_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sel])]).astype(np.int32)
+    col_idx = np.concatenate(sel).astype(np.int32)
+    O, lse = oracle.sparse_attention(Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets,
+                                     row_ptr, col_idx, perm_q=pq.perm)
+    _, lse_dense = oracle.dense_attention(Q, K, V)
+    for i in range(Cq):
+        rows = np.nonzero(lq == i)[0]
+        keys = np.nonzero(np.isin(lk, sel[i]))[0]
+        if rows.size == 0:
+            continue
+        np.testing.assert_allclose(O[rows], _sdpa(Q[rows], K[keys], V[keys]), rtol=1e-10, atol=1e-12)
+        assert np.all(lse[rows] <= lse_dense[rows] + 1e-12)
+        if len(sel[i]) == Ck:
+            np.testing.assert_allclose(lse[rows], lse_dense[rows], rtol=1e-12)
+    # a sampled subset of rows gives the same numbers and leaves the rest untouched
+    rows = np.array([3, 17, 64, 119], dtype=np.int32)
+    Os, _ = oracle.sparse_attention(Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets,
+                                    row_ptr, col_idx, perm_q=pq.perm, rows=rows)
+    np.testing.assert_array_equal(Os[pq.perm[rows]], O[pq.perm[rows]])
+    assert np.isnan(np.delete(Os, pq.perm[rows], axis=0)).all()
+
+
+def test_forward_with_top_p_one_is_dense_attention(oracle):
+    r = _rng(15)
+    N, d = 256, 16
+    Q, K, V = (r.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    res = oracle.forward(Q, K, V, Q[:6], K[:10], 3, 1.0, round_bf16=False)
+    np.testing.assert_allclose(res.O, _sdpa(Q, K, V), rtol=1e-10, atol=1e-12)
+    assert res.density == pytest.approx(1.0)
+    # and with top-p < 1 each row is library attention over its cluster's selected keys
+    res = oracle.forward(Q, K, V, Q[:6], K[:10], 3, 0.6, round_bf16=False)
+    assert 0.0 < res.density < 1.0
+    for i in range(6):
+        rows = np.nonzero(res.kq.labels == i)[0]
+        cols = res.sel.col_idx[res.sel.row_ptr[i]:res.sel.row_ptr[i + 1]]
+        keys = np.nonzero(np.isin(res.kk.labels, cols))[0]
+        if rows.size:
+            np.testing.assert_allclose(res.O[rows], _sdpa(Q[rows], K[keys], V[keys]), rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ accounting (Sections 4.2, 4.3, 5.1)
+
+def test_padding_example_printed_in_the_paper(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "padding_example.txt")) if l.strip() and l[0] != "#"]
+    for qr, kr, bm, bn, waste in rows:
+        assert oracle.padding_waste(int(qr), int(kr), int(bm), int(bn)) == pytest.approx(float(waste))
+    assert oracle.padding_waste(128, 128, 128, 128) == 0.0
+    assert oracle.padding_waste(129, 128, 128, 128) == pytest.approx(1 - 129 / 256)
+
+
+def test_identification_cost_bound_from_the_paper():
+    # Eq. 1 costs 2*Cq*Ck*d flops against 4*N*N*d for attention
+    for l in open(os.path.join(GOLDEN, "identification_cost.txt")):
+        if l.strip() and l[0] != "#":
+            N, Cq, Ck, bound = l.split()
+            assert 2 * int(Cq) * int(Ck) / (4 * int(N) ** 2) < float(bound)
