@@ -1,0 +1,184 @@
+/*
+ * svg2.h -- C ABI of the MI355X (gfx950) implementation of the per-layer
+ * sparse-attention path of Sparse VideoGen2 (arXiv 2505.18875):
+ *
+ *   k-means of Q and K tokens per head          Section 4.1
+ *   semantic-aware permutation                  Section 4.1
+ *   centroid-based top-p selection              Section 4.2, Eq. 1, Eq. 2
+ *   block-sparse attention, variable block size Section 4.3
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless the
+ *     comment says HOST.  Tensors are dense, row-major, innermost dimension
+ *     contiguous; a batch dimension is folded into H.  Nothing is retained
+ *     after a call returns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.  The
+ *     library allocates no device memory: scratch comes in through
+ *     (ws, ws_bytes), whose required size the matching *_workspace_size
+ *     function returns (0 is never returned; ws must be 256-byte aligned).
+ *   - Return value: SVG2_OK or an error code.  On any error nothing has been
+ *     launched and svg2_last_error() (thread-local, HOST string) says why.
+ *   - dtype is SVG2_F32 or SVG2_BF16 (storage type of Q, K, V, O); d is 64 or
+ *     128; 1 <= C <= min(N, SVG2_MAX_CLUSTERS); H >= 1; N >= 1 and
+ *     H*N*d < 2^40.  Accumulation is always fp32.
+ *   - Readings of the paper where it is silent: squared Euclidean distance;
+ *     one k-means iteration = assign then update; an empty cluster keeps its
+ *     centroid; argmin ties go to the lowest cluster index; for bf16 input
+ *     the assign step uses the centroids rounded to bf16 (returned centroids
+ *     stay fp32 means); tokens keep their original order inside a cluster;
+ *     top-p keeps the cluster whose mass crosses p; equal P' goes to the lower
+ *     index; empty key clusters are never selected; softmax is renormalised
+ *     over the selected keys.
+ */
+#ifndef SVG2_H
+#define SVG2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SVG2_MAX_CLUSTERS 4096
+
+enum {
+    SVG2_OK = 0,
+    SVG2_INVALID_ARG = 1,          /* null pointer, size out of range, ... */
+    SVG2_UNSUPPORTED = 2,          /* dtype or head dimension not built    */
+    SVG2_WORKSPACE_TOO_SMALL = 3,
+    SVG2_HIP_ERROR = 4             /* a HIP runtime call failed            */
+};
+
+enum { SVG2_F32 = 0, SVG2_BF16 = 1 };
+
+/* HOST string describing the last error on the calling thread ("" if none). */
+const char *svg2_last_error(void);
+
+/* Library version, major*100 + minor. */
+int svg2_version(void);
+
+/* ---------------------------------------------------------------------------
+ * svg2_kmeans -- Section 4.1: Lloyd k-means, independently for each head.
+ *   X              [H,N,d] dtype          tokens (Q or K of one layer)
+ *   init_centroids [H,C,d] fp32           required; pass last step's output to
+ *                                         warm-start (centroid cache, Section 4.3)
+ *   centroids      [H,C,d] fp32  out      means of the returned clusters; may
+ *                                         alias init_centroids
+ *   labels         [H,N]   int32 out      cluster of each token (last assign)
+ *   counts         [H,C]   int32 out      cluster sizes |Q_i| / |K_j|
+ *   objective      [H,iters] fp32 out or NULL: sum of squared distances right
+ *                                         after each assign step
+ *   iters >= 1 iterations of (assign, update).
+ * ------------------------------------------------------------------------- */
+size_t svg2_kmeans_workspace_size(int dtype, int H, int N, int d, int C);
+int svg2_kmeans(const void *X, int dtype, int H, int N, int d, int C, int iters,
+                const float *init_centroids, float *centroids, int32_t *labels,
+                int32_t *counts, float *objective,
+                void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_permute -- Section 4.1: the permutation pi that makes every cluster
+ * contiguous, as an index vector, and its application to up to two tensors
+ * (K and V share pi_k).
+ *   labels   [H,N]   int32            values in [0,C)
+ *   offsets  [H,C+1] int32 out        cluster c occupies sorted rows
+ *                                     offsets[c] .. offsets[c+1]; offsets[C] = N
+ *   perm     [H,N]   int32 out        sorted row r holds original token perm[r]
+ *                                     (clusters ascending, stable inside)
+ *   inv_perm [H,N]   int32 out or NULL  inv_perm[perm[r]] = r
+ *   n_tensors in 0..2; src, dst: HOST arrays of n_tensors DEVICE pointers,
+ *   each [H,N,d] dtype; dst[t][h,r,:] = src[t][h,perm[h,r],:].  dst must not
+ *   overlap src.  With n_tensors = 0, src/dst/dtype/d are ignored.
+ *   A label outside [0,C) is undefined behaviour (it is the output of
+ *   svg2_kmeans in the intended use).
+ * ------------------------------------------------------------------------- */
+size_t svg2_permute_workspace_size(int H, int N, int C);
+int svg2_permute(const int32_t *labels, int H, int N, int C,
+                 int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                 int n_tensors, const void *const *src, void *const *dst,
+                 int dtype, int d, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_select_topp -- Section 4.2: S_ij = cq_i . ck_j / sqrt(d) (Eq. 1),
+ * P'_ij = |K_j| exp(S_ij) / sum_k |K_k| exp(S_ik) (Eq. 2); for each query
+ * cluster the key clusters are taken in descending P' until the accumulated
+ * P' reaches top_p (0 < top_p <= 1; top_p = 1 keeps every non-empty cluster).
+ *   cq [H,Cq,d], ck [H,Ck,d] fp32     centroids
+ *   counts_q [H,Cq] int32 or NULL     query clusters of size 0 get an empty row
+ *   counts_k [H,Ck] int32             |K_j|
+ *   row_ptr  [H,Cq+1] int32 out       CSR row pointers, relative to the head's
+ *                                     segment of col_idx (row_ptr[h,0] = 0)
+ *   col_idx  [H,Cq*Ck] int32 out      head h owns entries h*Cq*Ck ...; selected
+ *                                     key clusters of row i, ascending
+ *   p_est    [H,Cq,Ck] fp32 out or NULL   P'
+ *   density  [H] fp32 out or NULL     sum over selected pairs |Q_i||K_j| /
+ *                                     (N_q N_k) (Section 5.1); needs counts_q
+ * ------------------------------------------------------------------------- */
+size_t svg2_select_topp_workspace_size(int H, int Cq, int Ck);
+int svg2_select_topp(const float *cq, const float *ck,
+                     const int32_t *counts_q, const int32_t *counts_k,
+                     int H, int Cq, int Ck, int d, float top_p,
+                     int32_t *row_ptr, int32_t *col_idx, float *p_est, float *density,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_sparse_attn -- Section 4.3: every row of query cluster i attends, with
+ * an ordinary softmax, over the keys of the key clusters selected for i.
+ *   Qp, Kp, Vp [H,N,d] dtype          permuted tensors (clusters contiguous)
+ *   offsets_q [H,Cq+1], offsets_k [H,Ck+1], row_ptr [H,Cq+1],
+ *   col_idx [H,Cq*Ck]                 as produced by svg2_permute / svg2_select_topp
+ *   perm_q [H,N] int32 or NULL        result of sorted row r is stored at row
+ *                                     perm_q[r] (the inverse permutation of
+ *                                     Section 4.1); NULL leaves sorted order
+ *   scale <= 0 means 1/sqrt(d)
+ *   O   [H,N,d] dtype out; lse [H,N] fp32 out or NULL (natural log of the
+ *   softmax denominator, -inf for a row with no selected key, whose O is 0).
+ *   Dense attention is the special case Cq = Ck = 1, row_ptr = {0,1},
+ *   col_idx = {0}, offsets = {0,N}.
+ * ------------------------------------------------------------------------- */
+size_t svg2_sparse_attn_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck);
+int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype,
+                     int H, int N, int d, int Cq, int Ck,
+                     const int32_t *offsets_q, const int32_t *offsets_k,
+                     const int32_t *row_ptr, const int32_t *col_idx,
+                     const int32_t *perm_q, float scale, void *O, float *lse,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_forward -- the whole layer (Section 4): k-means of Q and of K,
+ * both permutations, selection, sparse attention, output in original order.
+ *   Q, K, V [H,N,d] dtype; O [H,N,d] dtype out
+ *   cq_inout [H,Cq,d], ck_inout [H,Ck,d] fp32: initial centroids in, final
+ *   centroids out -- pass the same buffers at the next denoising step to
+ *   warm-start it (centroid cache, Section 4.3).
+ *   aux: HOST struct or NULL.  A non-NULL member is a DEVICE buffer that
+ *   receives that intermediate result; a NULL member lives in the workspace.
+ * ------------------------------------------------------------------------- */
+typedef struct svg2_forward_aux {
+    int32_t *labels_q;   /* [H,N]     */
+    int32_t *labels_k;   /* [H,N]     */
+    int32_t *counts_q;   /* [H,Cq]    */
+    int32_t *counts_k;   /* [H,Ck]    */
+    int32_t *offsets_q;  /* [H,Cq+1]  */
+    int32_t *offsets_k;  /* [H,Ck+1]  */
+    int32_t *perm_q;     /* [H,N]     */
+    int32_t *perm_k;     /* [H,N]     */
+    int32_t *row_ptr;    /* [H,Cq+1]  */
+    int32_t *col_idx;    /* [H,Cq*Ck] */
+    float *density;      /* [H]       */
+    float *lse;          /* [H,N]     */
+} svg2_forward_aux;
+
+size_t svg2_forward_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck);
+int svg2_forward(const void *Q, const void *K, const void *V, int dtype,
+                 int H, int N, int d, int Cq, int Ck, float top_p, int iters,
+                 float *cq_inout, float *ck_inout, void *O,
+                 const svg2_forward_aux *aux,
+                 void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVG2_H */

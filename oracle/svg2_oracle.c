@@ -227,8 +227,8 @@ void svg2o_gather_rows(const float *X, const int32_t *perm, int N, int d, float 
  * Outputs: row_ptr [Cq+1], col_idx [capacity Cq*Ck] ascending inside a row,
  * p_est [Cq,Ck] or NULL, margin [Cq] or NULL (how far the stopping decision
  * of the row is from flipping: min of |sum before last kept - p|, |sum
- * including last kept - p| and the P' gap between last kept and first
- * dropped), density (Section 5.1; needs counts_q, else NaN).
+ * including last kept - p| and the relative P' gap between last kept and
+ * first dropped), density (Section 5.1; needs counts_q, else NaN).
  * ------------------------------------------------------------------------ */
 typedef struct { double p; int j; } svg2o_pj;
 
@@ -297,7 +297,7 @@ void svg2o_select_topp(const double *cq, const double *ck,
                 if (n_kept > 0) {
                     double before = cum - last;
                     mg = fmin(fabs(before - top_p), fabs(cum - top_p));
-                    if (first_dropped >= 0.0) mg = fmin(mg, last - first_dropped);
+                    if (first_dropped >= 0.0 && last > 0.0) mg = fmin(mg, (last - first_dropped) / last);
                 }
             }
         }

@@ -1,0 +1,11 @@
+"""MI355X (gfx950) implementation of the Sparse VideoGen2 sparse-attention layer path.
+
+The product is the C-ABI library `libsvg2_hip.so` (see include/svg2.h); this
+package holds its HIP sources (csrc/), the build step (build.py), a ctypes
+binding with the same entry-point names (binding.py) and the synthetic input
+generators (workloads.py).
+"""
+from .binding import (  # noqa: F401
+    SVG2_BF16, SVG2_F32, Svg2Error, load_library, svg2_forward, svg2_forward_workspace_size,
+    svg2_kmeans, svg2_permute, svg2_select_topp, svg2_sparse_attn,
+)

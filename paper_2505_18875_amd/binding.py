@@ -1,0 +1,232 @@
+"""Thin ctypes binding of libsvg2_hip.so (include/svg2.h).
+
+Argument marshalling only: tensors are torch CUDA(=HIP) tensors used as device
+buffers, outputs and the workspace are allocated with torch, the current torch
+stream is passed through, and every step of the path runs in the library's
+kernels.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from types import SimpleNamespace
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvg2_hip.so")
+
+SVG2_F32, SVG2_BF16 = 0, 1
+SVG2_OK = 0
+MAX_CLUSTERS = 4096
+
+EXPORTS = (
+    "svg2_last_error", "svg2_version",
+    "svg2_kmeans_workspace_size", "svg2_kmeans",
+    "svg2_permute_workspace_size", "svg2_permute",
+    "svg2_select_topp_workspace_size", "svg2_select_topp",
+    "svg2_sparse_attn_workspace_size", "svg2_sparse_attn",
+    "svg2_forward_workspace_size", "svg2_forward",
+)
+
+
+class Svg2Error(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("svg2 error %d: %s" % (code, msg))
+        self.code = code
+
+
+class _ForwardAux(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "labels_q", "labels_k", "counts_q", "counts_k", "offsets_q", "offsets_k",
+        "perm_q", "perm_k", "row_ptr", "col_idx", "density", "lse")]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the C-ABI library; raises if it has not been built (python -m paper_2505_18875_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it with `python paper_2505_18875_amd/build.py` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.svg2_last_error.restype = ctypes.c_char_p
+        lib.svg2_version.restype = ctypes.c_int
+        for n in EXPORTS:
+            if n.endswith("_workspace_size"):
+                getattr(lib, n).restype = ctypes.c_size_t
+        vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        lib.svg2_kmeans_workspace_size.argtypes = [i, i, i, i, i]
+        lib.svg2_kmeans.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.svg2_permute_workspace_size.argtypes = [i, i, i]
+        lib.svg2_permute.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, i, i, vp, sz, vp]
+        lib.svg2_select_topp_workspace_size.argtypes = [i, i, i]
+        lib.svg2_select_topp.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, vp, vp, vp, sz, vp]
+        lib.svg2_sparse_attn_workspace_size.argtypes = [i, i, i, i, i, i]
+        lib.svg2_sparse_attn.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, f, vp, vp, vp, sz, vp]
+        lib.svg2_forward_workspace_size.argtypes = [i, i, i, i, i, i]
+        lib.svg2_forward.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, vp, sz, vp]
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != SVG2_OK:
+        raise Svg2Error(rc, load_library().svg2_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SVG2_F32
+    if t.dtype == torch.bfloat16:
+        return SVG2_BF16
+    raise TypeError("svg2 supports float32 and bfloat16 tensors, got %s" % t.dtype)
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def svg2_kmeans(X, init_centroids, iters, *, centroids=None, want_objective=False, ws=None):
+    """Section 4.1.  X [H,N,d]; init_centroids [H,C,d] fp32 -> centroids, labels, counts (, objective)."""
+    lib = load_library()
+    H, N, d = X.shape
+    C = init_centroids.shape[1]
+    dt = _dtype_code(X)
+    dev = X.device
+    centroids = torch.empty_like(init_centroids) if centroids is None else centroids
+    labels = torch.empty((H, N), dtype=torch.int32, device=dev)
+    counts = torch.empty((H, C), dtype=torch.int32, device=dev)
+    objective = torch.empty((H, iters), dtype=torch.float32, device=dev) if want_objective else None
+    need = lib.svg2_kmeans_workspace_size(dt, H, N, d, C)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_kmeans(_dev(X, name="X"), dt, H, N, d, C, int(iters),
+                           _dev(init_centroids, torch.float32, "init_centroids"),
+                           _dev(centroids, torch.float32, "centroids"), _dev(labels), _dev(counts),
+                           _dev(objective), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(centroids=centroids, labels=labels, counts=counts, objective=objective)
+
+
+def svg2_permute(labels, C, tensors=(), *, want_inverse=True, ws=None):
+    """Section 4.1.  labels [H,N] int32 -> offsets, perm, inv_perm and the permuted copies of `tensors`."""
+    lib = load_library()
+    H, N = labels.shape
+    dev = labels.device
+    offsets = torch.empty((H, C + 1), dtype=torch.int32, device=dev)
+    perm = torch.empty((H, N), dtype=torch.int32, device=dev)
+    inv = torch.empty((H, N), dtype=torch.int32, device=dev) if want_inverse else None
+    n = len(tensors)
+    outs = [torch.empty_like(t) for t in tensors]
+    dt, d = (SVG2_F32, 0)
+    src = dst = None
+    if n:
+        dt, d = _dtype_code(tensors[0]), tensors[0].shape[-1]
+        for t in tensors:
+            if t.shape != (H, N, d) or _dtype_code(t) != dt:
+                raise ValueError("tensors must all be [H,N,d] of one dtype")
+            _dev(t, name="tensor")
+        src = (ctypes.c_void_p * n)(*[t.data_ptr() for t in tensors])
+        dst = (ctypes.c_void_p * n)(*[t.data_ptr() for t in outs])
+    need = lib.svg2_permute_workspace_size(H, N, C)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_permute(_dev(labels, torch.int32, "labels"), H, N, C, _dev(offsets), _dev(perm), _dev(inv),
+                            n, src, dst, dt, d, _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(offsets=offsets, perm=perm, inv_perm=inv, tensors=outs)
+
+
+def svg2_select_topp(cq, ck, counts_q, counts_k, top_p, *, want_p_est=False, ws=None):
+    """Section 4.2, Eq. 1-2 and the top-p rule -> CSR (row_ptr, col_idx), density (, p_est)."""
+    lib = load_library()
+    H, Cq, d = cq.shape
+    Ck = ck.shape[1]
+    dev = cq.device
+    row_ptr = torch.empty((H, Cq + 1), dtype=torch.int32, device=dev)
+    col_idx = torch.empty((H, Cq * Ck), dtype=torch.int32, device=dev)
+    p_est = torch.empty((H, Cq, Ck), dtype=torch.float32, device=dev) if want_p_est else None
+    density = torch.empty((H,), dtype=torch.float32, device=dev) if counts_q is not None else None
+    need = lib.svg2_select_topp_workspace_size(H, Cq, Ck)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_select_topp(_dev(cq, torch.float32, "cq"), _dev(ck, torch.float32, "ck"),
+                                _dev(counts_q, torch.int32, "counts_q"), _dev(counts_k, torch.int32, "counts_k"),
+                                H, Cq, Ck, d, float(top_p), _dev(row_ptr), _dev(col_idx), _dev(p_est),
+                                _dev(density), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(row_ptr=row_ptr, col_idx=col_idx, p_est=p_est, density=density)
+
+
+def svg2_sparse_attn(Qp, Kp, Vp, offsets_q, offsets_k, row_ptr, col_idx, perm_q=None, *, scale=0.0,
+                     want_lse=False, out=None, ws=None):
+    """Section 4.3.  Permuted Q, K, V [H,N,d] + block list -> O [H,N,d] (original order if perm_q is given)."""
+    lib = load_library()
+    H, N, d = Qp.shape
+    Cq, Ck = offsets_q.shape[1] - 1, offsets_k.shape[1] - 1
+    dt = _dtype_code(Qp)
+    dev = Qp.device
+    if col_idx.numel() < H * Cq * Ck:
+        raise ValueError("col_idx must have capacity H*Cq*Ck")
+    O = torch.empty_like(Qp) if out is None else out
+    lse = torch.empty((H, N), dtype=torch.float32, device=dev) if want_lse else None
+    need = lib.svg2_sparse_attn_workspace_size(dt, H, N, d, Cq, Ck)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_sparse_attn(_dev(Qp, name="Qp"), _dev(Kp, Qp.dtype, "Kp"), _dev(Vp, Qp.dtype, "Vp"), dt, H, N, d,
+                                Cq, Ck, _dev(offsets_q, torch.int32, "offsets_q"),
+                                _dev(offsets_k, torch.int32, "offsets_k"), _dev(row_ptr, torch.int32, "row_ptr"),
+                                _dev(col_idx, torch.int32, "col_idx"), _dev(perm_q, torch.int32, "perm_q"),
+                                float(scale), _dev(O, Qp.dtype, "O"), _dev(lse), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(O=O, lse=lse)
+
+
+def svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck) -> int:
+    return load_library().svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck)
+
+
+def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, out=None, ws=None):
+    """Section 4, the whole layer.  cq_inout / ck_inout [H,C,d] fp32 are updated in place (centroid cache)."""
+    lib = load_library()
+    H, N, d = Q.shape
+    Cq, Ck = cq_inout.shape[1], ck_inout.shape[1]
+    dt = _dtype_code(Q)
+    dev = Q.device
+    O = torch.empty_like(Q) if out is None else out
+    aux_t = None
+    aux_p = None
+    if want_aux:
+        i32 = dict(dtype=torch.int32, device=dev)
+        aux_t = SimpleNamespace(
+            labels_q=torch.empty((H, N), **i32), labels_k=torch.empty((H, N), **i32),
+            counts_q=torch.empty((H, Cq), **i32), counts_k=torch.empty((H, Ck), **i32),
+            offsets_q=torch.empty((H, Cq + 1), **i32), offsets_k=torch.empty((H, Ck + 1), **i32),
+            perm_q=torch.empty((H, N), **i32), perm_k=torch.empty((H, N), **i32),
+            row_ptr=torch.empty((H, Cq + 1), **i32), col_idx=torch.empty((H, Cq * Ck), **i32),
+            density=torch.empty((H,), dtype=torch.float32, device=dev),
+            lse=torch.empty((H, N), dtype=torch.float32, device=dev))
+        aux_s = _ForwardAux(**{n: getattr(aux_t, n).data_ptr() for n, _ in _ForwardAux._fields_})
+        aux_p = ctypes.cast(ctypes.pointer(aux_s), ctypes.c_void_p)
+    need = lib.svg2_forward_workspace_size(dt, H, N, d, Cq, Ck)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_forward(_dev(Q, name="Q"), _dev(K, Q.dtype, "K"), _dev(V, Q.dtype, "V"), dt, H, N, d, Cq, Ck,
+                            float(top_p), int(iters), _dev(cq_inout, torch.float32, "cq_inout"),
+                            _dev(ck_inout, torch.float32, "ck_inout"), _dev(O, Q.dtype, "O"), aux_p,
+                            _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(O=O, aux=aux_t)

@@ -1,0 +1,270 @@
+// C ABI of the gfx950 SVG2 library: argument validation, workspace carving and
+// the whole-layer entry point.  Every check happens before anything is
+// launched, so an error code means no work was enqueued.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "svg2_common.h"
+
+namespace svg2 {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+static int check_common(int dtype, int H, int N, int d)
+{
+    SVG2_REQUIRE(dtype == SVG2_F32 || dtype == SVG2_BF16, SVG2_UNSUPPORTED, "dtype %d is not SVG2_F32 or SVG2_BF16", dtype);
+    SVG2_REQUIRE(d == 64 || d == 128, SVG2_UNSUPPORTED, "head dimension %d is not 64 or 128", d);
+    SVG2_REQUIRE(H >= 1 && N >= 1, SVG2_INVALID_ARG, "H = %d and N = %d must be positive", H, N);
+    SVG2_REQUIRE((double)H * (double)N * (double)d < 1099511627776.0, SVG2_INVALID_ARG, "H*N*d is 2^40 or more");
+    SVG2_REQUIRE(H <= 65535, SVG2_INVALID_ARG, "H = %d exceeds 65535", H);
+    return SVG2_OK;
+}
+
+static int check_clusters(const char *name, int C, int N)
+{
+    SVG2_REQUIRE(C >= 1 && C <= SVG2_MAX_CLUSTERS && C <= N, SVG2_INVALID_ARG,
+                 "%s = %d must be in 1..min(N = %d, %d)", name, C, N, SVG2_MAX_CLUSTERS);
+    return SVG2_OK;
+}
+
+static int check_ws(const void *ws, size_t have, size_t need)
+{
+    SVG2_REQUIRE(ws != nullptr, SVG2_INVALID_ARG, "workspace pointer is null");
+    SVG2_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255) == 0, SVG2_INVALID_ARG, "workspace is not 256-byte aligned");
+    SVG2_REQUIRE(have >= need, SVG2_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", have, need);
+    return SVG2_OK;
+}
+
+#define SVG2_TRY(expr)                    \
+    do {                                  \
+        int rc_ = (expr);                 \
+        if (rc_ != SVG2_OK) return rc_;   \
+    } while (0)
+
+// Layout of svg2_forward's workspace.
+struct ForwardLayout {
+    int32_t *labels_q, *labels_k, *counts_q, *counts_k, *offsets_q, *offsets_k, *perm_q, *perm_k, *row_ptr, *col_idx;
+    float *density;
+    void *Qp, *Kp, *Vp;
+    void *stage_ws;
+    size_t stage_bytes, total;
+};
+
+static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, int Cq, int Ck)
+{
+    ForwardLayout L;
+    Carver c(ws);
+    const size_t es = dtype == SVG2_BF16 ? 2 : 4;
+    L.labels_q = c.take<int32_t>((size_t)H * N);
+    L.labels_k = c.take<int32_t>((size_t)H * N);
+    L.counts_q = c.take<int32_t>((size_t)H * Cq);
+    L.counts_k = c.take<int32_t>((size_t)H * Ck);
+    L.offsets_q = c.take<int32_t>((size_t)H * (Cq + 1));
+    L.offsets_k = c.take<int32_t>((size_t)H * (Ck + 1));
+    L.perm_q = c.take<int32_t>((size_t)H * N);
+    L.perm_k = c.take<int32_t>((size_t)H * N);
+    L.row_ptr = c.take<int32_t>((size_t)H * (Cq + 1));
+    L.col_idx = c.take<int32_t>((size_t)H * Cq * Ck);
+    L.density = c.take<float>((size_t)H);
+    L.Qp = c.take<char>((size_t)H * N * d * es);
+    L.Kp = c.take<char>((size_t)H * N * d * es);
+    L.Vp = c.take<char>((size_t)H * N * d * es);
+    // the stages run one after another on one stream and share one scratch area
+    size_t s = kmeans_ws_bytes(dtype, H, N, d, Cq);
+    size_t t = kmeans_ws_bytes(dtype, H, N, d, Ck);
+    if (t > s) s = t;
+    t = permute_ws_bytes(H, N, Cq > Ck ? Cq : Ck);
+    if (t > s) s = t;
+    t = select_ws_bytes(H, Cq, Ck);
+    if (t > s) s = t;
+    t = attn_ws_bytes(dtype, H, N, d, Cq, Ck);
+    if (t > s) s = t;
+    L.stage_bytes = s;
+    L.stage_ws = c.take<char>(s);
+    L.total = c.used;
+    return L;
+}
+
+}  // namespace svg2
+
+using namespace svg2;
+
+extern "C" {
+
+const char *svg2_last_error(void) { return g_err; }
+
+int svg2_version(void) { return 100; }
+
+size_t svg2_kmeans_workspace_size(int dtype, int H, int N, int d, int C)
+{
+    if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("C", C, N) != SVG2_OK) return 256;
+    return kmeans_ws_bytes(dtype, H, N, d, C);
+}
+
+int svg2_kmeans(const void *X, int dtype, int H, int N, int d, int C, int iters, const float *init_centroids,
+                float *centroids, int32_t *labels, int32_t *counts, float *objective, void *ws, size_t ws_bytes,
+                void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_clusters("C", C, N));
+    SVG2_REQUIRE(iters >= 1, SVG2_INVALID_ARG, "iters = %d must be at least 1", iters);
+    SVG2_REQUIRE(X && init_centroids && centroids && labels && counts, SVG2_INVALID_ARG,
+                 "X, init_centroids, centroids, labels and counts must be non-null");
+    SVG2_TRY(check_ws(ws, ws_bytes, kmeans_ws_bytes(dtype, H, N, d, C)));
+    return kmeans_launch(X, dtype, H, N, d, C, iters, init_centroids, centroids, labels, counts, objective, ws,
+                         static_cast<hipStream_t>(stream));
+}
+
+size_t svg2_permute_workspace_size(int H, int N, int C)
+{
+    if (H < 1 || N < 1 || C < 1 || C > SVG2_MAX_CLUSTERS) return 256;
+    return permute_ws_bytes(H, N, C);
+}
+
+int svg2_permute(const int32_t *labels, int H, int N, int C, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                 int n_tensors, const void *const *src, void *const *dst, int dtype, int d, void *ws,
+                 size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_REQUIRE(H >= 1 && H <= 65535 && N >= 1, SVG2_INVALID_ARG, "H = %d (1..65535) and N = %d must be positive", H, N);
+    SVG2_REQUIRE(C >= 1 && C <= SVG2_MAX_CLUSTERS, SVG2_INVALID_ARG, "C = %d must be in 1..%d", C, SVG2_MAX_CLUSTERS);
+    SVG2_REQUIRE(labels && offsets && perm, SVG2_INVALID_ARG, "labels, offsets and perm must be non-null");
+    SVG2_REQUIRE(n_tensors >= 0 && n_tensors <= 2, SVG2_INVALID_ARG, "n_tensors = %d must be 0, 1 or 2", n_tensors);
+    if (n_tensors > 0) {
+        SVG2_TRY(check_common(dtype, H, N, d));
+        SVG2_REQUIRE(src && dst, SVG2_INVALID_ARG, "src and dst must be non-null when n_tensors > 0");
+        for (int t = 0; t < n_tensors; ++t) {
+            SVG2_REQUIRE(src[t] && dst[t], SVG2_INVALID_ARG, "src[%d] / dst[%d] is null", t, t);
+            SVG2_REQUIRE(src[t] != dst[t], SVG2_INVALID_ARG, "dst[%d] must not alias src[%d]", t, t);
+        }
+    }
+    SVG2_TRY(check_ws(ws, ws_bytes, permute_ws_bytes(H, N, C)));
+    return permute_launch(labels, H, N, C, offsets, perm, inv_perm, n_tensors, src, dst, dtype, d, ws,
+                          static_cast<hipStream_t>(stream));
+}
+
+size_t svg2_select_topp_workspace_size(int H, int Cq, int Ck)
+{
+    if (H < 1 || Cq < 1 || Ck < 1 || Cq > SVG2_MAX_CLUSTERS || Ck > SVG2_MAX_CLUSTERS) return 256;
+    return select_ws_bytes(H, Cq, Ck);
+}
+
+int svg2_select_topp(const float *cq, const float *ck, const int32_t *counts_q, const int32_t *counts_k, int H,
+                     int Cq, int Ck, int d, float top_p, int32_t *row_ptr, int32_t *col_idx, float *p_est,
+                     float *density, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_REQUIRE(H >= 1 && H <= 65535, SVG2_INVALID_ARG, "H = %d must be in 1..65535", H);
+    SVG2_REQUIRE(d == 64 || d == 128, SVG2_UNSUPPORTED, "head dimension %d is not 64 or 128", d);
+    SVG2_REQUIRE(Cq >= 1 && Cq <= SVG2_MAX_CLUSTERS && Ck >= 1 && Ck <= SVG2_MAX_CLUSTERS, SVG2_INVALID_ARG,
+                 "Cq = %d and Ck = %d must be in 1..%d", Cq, Ck, SVG2_MAX_CLUSTERS);
+    SVG2_REQUIRE(top_p > 0.f && top_p <= 1.f, SVG2_INVALID_ARG, "top_p = %g must be in (0, 1]", (double)top_p);
+    SVG2_REQUIRE(cq && ck && counts_k && row_ptr && col_idx, SVG2_INVALID_ARG,
+                 "cq, ck, counts_k, row_ptr and col_idx must be non-null");
+    SVG2_REQUIRE(!density || counts_q, SVG2_INVALID_ARG, "density needs counts_q");
+    SVG2_TRY(check_ws(ws, ws_bytes, select_ws_bytes(H, Cq, Ck)));
+    return select_launch(cq, ck, counts_q, counts_k, H, Cq, Ck, d, top_p, row_ptr, col_idx, p_est, density, ws,
+                         static_cast<hipStream_t>(stream));
+}
+
+size_t svg2_sparse_attn_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
+{
+    if (check_common(dtype, H, N, d) != SVG2_OK || Cq < 1 || Ck < 1 || Cq > SVG2_MAX_CLUSTERS ||
+        Ck > SVG2_MAX_CLUSTERS)
+        return 256;
+    return attn_ws_bytes(dtype, H, N, d, Cq, Ck);
+}
+
+int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
+                     const int32_t *offsets_q, const int32_t *offsets_k, const int32_t *row_ptr,
+                     const int32_t *col_idx, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
+                     size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_clusters("Cq", Cq, N));
+    SVG2_TRY(check_clusters("Ck", Ck, N));
+    SVG2_REQUIRE(Qp && Kp && Vp && O && offsets_q && offsets_k && row_ptr && col_idx, SVG2_INVALID_ARG,
+                 "Qp, Kp, Vp, O, offsets_q, offsets_k, row_ptr and col_idx must be non-null");
+    SVG2_REQUIRE(O != Qp && O != Kp && O != Vp, SVG2_INVALID_ARG, "O must not alias an input");
+    SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(dtype, H, N, d, Cq, Ck)));
+    return attn_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, scale, O,
+                       lse, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t svg2_forward_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
+{
+    if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("Cq", Cq, N) != SVG2_OK ||
+        check_clusters("Ck", Ck, N) != SVG2_OK)
+        return 256;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck).total;
+}
+
+int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
+                 float top_p, int iters, float *cq_inout, float *ck_inout, void *O, const svg2_forward_aux *aux,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_clusters("Cq", Cq, N));
+    SVG2_TRY(check_clusters("Ck", Ck, N));
+    SVG2_REQUIRE(iters >= 1, SVG2_INVALID_ARG, "iters = %d must be at least 1", iters);
+    SVG2_REQUIRE(top_p > 0.f && top_p <= 1.f, SVG2_INVALID_ARG, "top_p = %g must be in (0, 1]", (double)top_p);
+    SVG2_REQUIRE(Q && K && V && O && cq_inout && ck_inout, SVG2_INVALID_ARG,
+                 "Q, K, V, O, cq_inout and ck_inout must be non-null");
+    SVG2_REQUIRE(O != Q && O != K && O != V, SVG2_INVALID_ARG, "O must not alias an input");
+    SVG2_REQUIRE(ws != nullptr, SVG2_INVALID_ARG, "workspace pointer is null");
+    ForwardLayout L = forward_layout(ws, dtype, H, N, d, Cq, Ck);
+    SVG2_TRY(check_ws(ws, ws_bytes, L.total));
+    float *lse = nullptr;
+    if (aux) {
+        if (aux->labels_q) L.labels_q = aux->labels_q;
+        if (aux->labels_k) L.labels_k = aux->labels_k;
+        if (aux->counts_q) L.counts_q = aux->counts_q;
+        if (aux->counts_k) L.counts_k = aux->counts_k;
+        if (aux->offsets_q) L.offsets_q = aux->offsets_q;
+        if (aux->offsets_k) L.offsets_k = aux->offsets_k;
+        if (aux->perm_q) L.perm_q = aux->perm_q;
+        if (aux->perm_k) L.perm_k = aux->perm_k;
+        if (aux->row_ptr) L.row_ptr = aux->row_ptr;
+        if (aux->col_idx) L.col_idx = aux->col_idx;
+        if (aux->density) L.density = aux->density;
+        lse = aux->lse;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Section 4.1: cluster Q and K independently
+    SVG2_TRY(kmeans_launch(Q, dtype, H, N, d, Cq, iters, cq_inout, cq_inout, L.labels_q, L.counts_q, nullptr,
+                           L.stage_ws, st));
+    SVG2_TRY(kmeans_launch(K, dtype, H, N, d, Ck, iters, ck_inout, ck_inout, L.labels_k, L.counts_k, nullptr,
+                           L.stage_ws, st));
+    // Section 4.1: permutations; K and V share pi_k
+    const void *src_q[1] = {Q};
+    void *dst_q[1] = {L.Qp};
+    SVG2_TRY(permute_launch(L.labels_q, H, N, Cq, L.offsets_q, L.perm_q, nullptr, 1, src_q, dst_q, dtype, d,
+                            L.stage_ws, st));
+    const void *src_k[2] = {K, V};
+    void *dst_k[2] = {L.Kp, L.Vp};
+    SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, 2, src_k, dst_k, dtype, d,
+                            L.stage_ws, st));
+    // Section 4.2: which (query cluster, key cluster) pairs to compute
+    SVG2_TRY(select_launch(cq_inout, ck_inout, L.counts_q, L.counts_k, H, Cq, Ck, d, top_p, L.row_ptr, L.col_idx,
+                           nullptr, L.density, L.stage_ws, st));
+    // Section 4.3: attention over the selected pairs, result back in token order
+    return attn_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx,
+                       L.perm_q, 0.f, O, lse, L.stage_ws, st);
+}
+
+}  // extern "C"

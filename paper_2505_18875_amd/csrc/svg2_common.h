@@ -1,0 +1,92 @@
+// Shared host/device helpers of the gfx950 SVG2 library (internal header).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "svg2.h"
+
+namespace svg2 {
+
+// ---- error reporting -------------------------------------------------------
+int fail(int code, const char *fmt, ...);      // records the message, returns code
+void clear_error();
+
+#define SVG2_REQUIRE(cond, code, ...)                         \
+    do {                                                      \
+        if (!(cond)) return ::svg2::fail((code), __VA_ARGS__); \
+    } while (0)
+
+#define SVG2_HIP_CHECK(expr)                                                        \
+    do {                                                                            \
+        hipError_t e_ = (expr);                                                     \
+        if (e_ != hipSuccess)                                                       \
+            return ::svg2::fail(SVG2_HIP_ERROR, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- workspace carving -----------------------------------------------------
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+struct Carver {
+    char *base;
+    size_t used;
+    explicit Carver(void *p) : base(static_cast<char *>(p)), used(0) {}
+    template <typename T> T *take(size_t n)
+    {
+        T *r = base ? reinterpret_cast<T *>(base + used) : nullptr;
+        used += align256(n * sizeof(T));
+        return r;
+    }
+};
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// ---- bf16 ------------------------------------------------------------------
+typedef unsigned short bf16_t;          // raw bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((unsigned)b) << 16); }
+
+// round to nearest, ties to even (inputs are finite here)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p) { return *p; }
+    static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- stage launchers (defined in the per-stage .hip files) -----------------
+// All of them assume validated arguments and a workspace of the right size.
+
+size_t kmeans_ws_bytes(int dtype, int H, int N, int d, int C);
+int kmeans_launch(const void *X, int dtype, int H, int N, int d, int C, int iters,
+                  const float *init, float *centroids, int32_t *labels, int32_t *counts,
+                  float *objective, void *ws, hipStream_t st);
+
+size_t permute_ws_bytes(int H, int N, int C);
+int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets, int32_t *perm,
+                   int32_t *inv_perm, int n_tensors, const void *const *src, void *const *dst,
+                   int dtype, int d, void *ws, hipStream_t st);
+
+size_t select_ws_bytes(int H, int Cq, int Ck);
+int select_launch(const float *cq, const float *ck, const int32_t *counts_q, const int32_t *counts_k,
+                  int H, int Cq, int Ck, int d, float top_p, int32_t *row_ptr, int32_t *col_idx,
+                  float *p_est, float *density, void *ws, hipStream_t st);
+
+size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck);
+int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d,
+                int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
+                const int32_t *row_ptr, const int32_t *col_idx, const int32_t *perm_q, float scale,
+                void *O, float *lse, void *ws, hipStream_t st);
+
+}  // namespace svg2

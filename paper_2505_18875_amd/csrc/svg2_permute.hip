@@ -1,0 +1,179 @@
+// Semantic-aware permutation (paper Section 4.1) as a stable counting sort of
+// token ids by cluster label, plus the row gather that applies it.
+//
+//   hist     per (head, chunk): histogram of labels              (LDS atomics)
+//   scan     per head: totals -> offsets (exclusive scan over clusters) and
+//            the first output slot of every (chunk, cluster)
+//   scatter  per (head, chunk): one wavefront walks its chunk in token order,
+//            ranking equal labels inside each group of 64 with ballots, so the
+//            order inside a cluster stays the original token order
+//   gather   dst[r,:] = src[perm[r],:], 16 bytes per lane, rows coalesced on
+//            the write side
+//
+// Everything is integer work: results are unique and reproducible bit for bit.
+#include "svg2_common.h"
+
+namespace svg2 {
+
+static constexpr int PERM_CHUNK = 2048;     // tokens per chunk (one wavefront in scatter)
+
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__restrict__ labels, int N, int C,
+                                                           int nchunks, int32_t *__restrict__ hist)
+{
+    extern __shared__ int32_t s_hist[];
+    const int chunk = blockIdx.x, h = blockIdx.y;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) s_hist[c] = 0;
+    __syncthreads();
+    const int n0 = chunk * PERM_CHUNK;
+    const int n1 = min(N, n0 + PERM_CHUNK);
+    const int32_t *lab = labels + (size_t)h * N;
+    for (int n = n0 + threadIdx.x; n < n1; n += blockDim.x) atomicAdd(&s_hist[lab[n]], 1);
+    __syncthreads();
+    int32_t *out = hist + ((size_t)h * nchunks + chunk) * C;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) out[c] = s_hist[c];
+}
+
+// One workgroup per head.  hist[h][k][c] becomes the first sorted row that
+// chunk k writes for cluster c.
+__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t *__restrict__ hist, int N, int C, int nchunks,
+                                                           int32_t *__restrict__ offsets)
+{
+    extern __shared__ int32_t s_tot[];                 // [C] totals, then exclusive offsets
+    __shared__ int32_t s_part[256];
+    const int h = blockIdx.x, tid = threadIdx.x;
+    int32_t *hh = hist + (size_t)h * nchunks * C;
+    for (int c = tid; c < C; c += 256) {
+        int run = 0;
+        for (int k = 0; k < nchunks; ++k) {
+            int v = hh[(size_t)k * C + c];
+            hh[(size_t)k * C + c] = run;
+            run += v;
+        }
+        s_tot[c] = run;
+    }
+    __syncthreads();
+    // exclusive scan of s_tot over c: each thread owns a contiguous slice
+    const int per = (C + 255) / 256;
+    const int c0 = min(C, tid * per), c1 = min(C, c0 + per);
+    int sum = 0;
+    for (int c = c0; c < c1; ++c) sum += s_tot[c];
+    s_part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int t = 0; t < 256; ++t) { int v = s_part[t]; s_part[t] = run; run += v; }
+    }
+    __syncthreads();
+    int run = s_part[tid];
+    for (int c = c0; c < c1; ++c) { int v = s_tot[c]; s_tot[c] = run; run += v; }
+    __syncthreads();
+    int32_t *off = offsets + (size_t)h * (C + 1);
+    for (int c = tid; c < C; c += 256) {
+        const int o = s_tot[c];
+        off[c] = o;
+        for (int k = 0; k < nchunks; ++k) hh[(size_t)k * C + c] += o;
+    }
+    if (tid == 0) off[C] = N;
+}
+
+__global__ __launch_bounds__(64) void permute_scatter_kernel(const int32_t *__restrict__ labels, int N, int C,
+                                                             int nchunks, int nbits,
+                                                             const int32_t *__restrict__ hist,
+                                                             int32_t *__restrict__ perm,
+                                                             int32_t *__restrict__ inv_perm)
+{
+    extern __shared__ int32_t s_cur[];                 // [C] next free sorted row per cluster
+    const int chunk = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t *base = hist + ((size_t)h * nchunks + chunk) * C;
+    for (int c = lane; c < C; c += 64) s_cur[c] = base[c];
+    __syncthreads();
+    const int32_t *lab = labels + (size_t)h * N;
+    int32_t *pm = perm + (size_t)h * N;
+    int32_t *ip = inv_perm ? inv_perm + (size_t)h * N : nullptr;
+    const int n0 = chunk * PERM_CHUNK;
+    const int n1 = min(N, n0 + PERM_CHUNK);
+    const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    for (int g = n0; g < n1; g += 64) {
+        const int n = g + lane;
+        const bool valid = n < n1;
+        const int l = valid ? lab[n] : 0;
+        // lanes holding the same label as this one
+        unsigned long long peers = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (l >> b) & 1;
+            const unsigned long long m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        int pos = 0;
+        if (valid) {
+            pos = s_cur[l] + __popcll(peers & lt_mask);
+            pm[pos] = n;
+            if (ip) ip[n] = pos;
+        }
+        __syncthreads();
+        // the first lane of every peer group advances that cluster's cursor
+        if (valid && (peers & lt_mask) == 0) s_cur[l] += __popcll(peers);
+        __syncthreads();
+    }
+}
+
+// dst[h, r, :] = src[h, perm[h, r], :] for up to two tensors; a row is
+// `lanes_per_row` lanes of 16 bytes.
+struct GatherPtrs {
+    const uint4 *src[2];
+    uint4 *dst[2];
+};
+
+__global__ __launch_bounds__(256) void permute_gather_kernel(GatherPtrs p, const int32_t *__restrict__ perm, int N,
+                                                             int lanes_per_row, int rows_per_block)
+{
+    const int h = blockIdx.y, t = blockIdx.z;
+    const uint4 *src = p.src[t] + (size_t)h * N * lanes_per_row;
+    uint4 *dst = p.dst[t] + (size_t)h * N * lanes_per_row;
+    const int32_t *pm = perm + (size_t)h * N;
+    const int r0 = blockIdx.x * rows_per_block;
+    const int r1 = min(N, r0 + rows_per_block);
+    const int rows_per_pass = 256 / lanes_per_row;
+    const int sub = threadIdx.x / lanes_per_row, part = threadIdx.x % lanes_per_row;
+    for (int r = r0 + sub; r < r1; r += rows_per_pass) {
+        const int s = pm[r];
+        dst[(size_t)r * lanes_per_row + part] = src[(size_t)s * lanes_per_row + part];
+    }
+}
+
+size_t permute_ws_bytes(int H, int N, int C)
+{
+    const int nchunks = cdiv(N, PERM_CHUNK);
+    return align256((size_t)H * nchunks * C * sizeof(int32_t));
+}
+
+int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets, int32_t *perm,
+                   int32_t *inv_perm, int n_tensors, const void *const *src, void *const *dst,
+                   int dtype, int d, void *ws, hipStream_t st)
+{
+    const int nchunks = cdiv(N, PERM_CHUNK);
+    int32_t *hist = static_cast<int32_t *>(ws);
+    int nbits = 0;
+    while ((1 << nbits) < C) ++nbits;
+    const size_t lds = (size_t)C * sizeof(int32_t);
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks, H), dim3(256), lds, st, labels, N, C, nchunks, hist);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(H), dim3(256), lds, st, hist, N, C, nchunks, offsets);
+    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nchunks, H), dim3(64), lds, st, labels, N, C, nchunks, nbits,
+                       hist, perm, inv_perm);
+    if (n_tensors > 0) {
+        GatherPtrs p = {};
+        for (int t = 0; t < n_tensors; ++t) {
+            p.src[t] = static_cast<const uint4 *>(src[t]);
+            p.dst[t] = static_cast<uint4 *>(dst[t]);
+        }
+        const int row_bytes = d * (dtype == SVG2_BF16 ? 2 : 4);
+        const int lanes_per_row = row_bytes / 16;
+        const int rows_per_block = 256;
+        hipLaunchKernelGGL(permute_gather_kernel, dim3(cdiv(N, rows_per_block), H, n_tensors), dim3(256), 0, st, p,
+                           perm, N, lanes_per_row, rows_per_block);
+    }
+    SVG2_HIP_CHECK(hipGetLastError());
+    return SVG2_OK;
+}
+
+}  // namespace svg2
