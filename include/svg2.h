@@ -178,6 +178,22 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype,
                  const svg2_forward_aux *aux,
                  void *ws, size_t ws_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * Stage timing for benchmarks (HOST-side state, one per process).
+ * svg2_profile_enable(1): every later svg2_forward call records HIP events
+ * around its stages on the caller's stream (events are created on first use;
+ * at most SVG2_PROFILE_MAX_CALLS calls are kept, later ones go unrecorded).
+ * svg2_profile_read waits for the recorded events, writes the summed
+ * milliseconds per stage to stage_ms (HOST array of SVG2_N_STAGES floats, in
+ * the order k-means Q, k-means K, permutation Q+K, selection, attention plan,
+ * attention kernel) and the number of recorded calls to n_calls (HOST), then
+ * clears the record.  svg2_profile_enable(0) stops recording.
+ * ------------------------------------------------------------------------- */
+#define SVG2_N_STAGES 6
+#define SVG2_PROFILE_MAX_CALLS 256
+int svg2_profile_enable(int enable);
+int svg2_profile_read(float *stage_ms, int *n_calls);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,9 @@ EXPORTS = (
     "svg2_select_topp_workspace_size", "svg2_select_topp",
     "svg2_sparse_attn_workspace_size", "svg2_sparse_attn",
     "svg2_forward_workspace_size", "svg2_forward",
+    "svg2_profile_enable", "svg2_profile_read",
 )
+STAGES = ("kmeans_q", "kmeans_k", "permute", "select", "attn_plan", "attn")
 
 
 class Svg2Error(RuntimeError):
@@ -72,6 +74,8 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_sparse_attn.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, f, vp, vp, vp, sz, vp]
         lib.svg2_forward_workspace_size.argtypes = [i, i, i, i, i, i]
         lib.svg2_forward.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, vp, sz, vp]
+        lib.svg2_profile_enable.argtypes = [i]
+        lib.svg2_profile_read.argtypes = [vp, vp]
         _lib = lib
     return _lib
 
@@ -230,3 +234,16 @@ def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, o
                             _dev(ck_inout, torch.float32, "ck_inout"), _dev(O, Q.dtype, "O"), aux_p,
                             _dev(ws), ws.numel(), _stream()))
     return SimpleNamespace(O=O, aux=aux_t)
+
+
+def svg2_profile_enable(enable: bool) -> None:
+    """Start / stop recording HIP events around the stages of svg2_forward."""
+    _check(load_library().svg2_profile_enable(int(bool(enable))))
+
+
+def svg2_profile_read():
+    """(dict stage -> summed milliseconds, number of recorded svg2_forward calls); clears the record."""
+    ms = (ctypes.c_float * len(STAGES))()
+    n = ctypes.c_int(0)
+    _check(load_library().svg2_profile_read(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(ctypes.pointer(n), ctypes.c_void_p)))
+    return {k: float(v) for k, v in zip(STAGES, ms)}, n.value

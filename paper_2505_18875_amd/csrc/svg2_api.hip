@@ -4,6 +4,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "svg2_common.h"
 
@@ -95,6 +97,34 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     L.stage_ws = c.take<char>(s);
     L.total = c.used;
     return L;
+}
+
+// ---- optional stage timing (svg2_profile_*) -----------------------------------
+struct Profiler {
+    std::mutex mu;
+    bool on = false;
+    int ncalls = 0;
+    std::vector<hipEvent_t> ev;          // (SVG2_N_STAGES + 1) events per recorded call
+};
+static Profiler g_prof;
+
+// Returns the event slot base for this call, or -1 when not recording.
+static int profile_begin_call()
+{
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (!g_prof.on || g_prof.ncalls >= SVG2_PROFILE_MAX_CALLS) return -1;
+    const size_t need = (size_t)(g_prof.ncalls + 1) * (SVG2_N_STAGES + 1);
+    while (g_prof.ev.size() < need) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return -1;
+        g_prof.ev.push_back(e);
+    }
+    return (g_prof.ncalls++) * (SVG2_N_STAGES + 1);
+}
+
+static void profile_mark(int base, int k, hipStream_t st)
+{
+    if (base >= 0) (void)hipEventRecord(g_prof.ev[base + k], st);
 }
 
 }  // namespace svg2
@@ -245,11 +275,15 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
         lse = aux->lse;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int pb = profile_begin_call();
+    profile_mark(pb, 0, st);
     // Section 4.1: cluster Q and K independently
     SVG2_TRY(kmeans_launch(Q, dtype, H, N, d, Cq, iters, cq_inout, cq_inout, L.labels_q, L.counts_q, nullptr,
                            L.stage_ws, st));
+    profile_mark(pb, 1, st);
     SVG2_TRY(kmeans_launch(K, dtype, H, N, d, Ck, iters, ck_inout, ck_inout, L.labels_k, L.counts_k, nullptr,
                            L.stage_ws, st));
+    profile_mark(pb, 2, st);
     // Section 4.1: permutations; K and V share pi_k
     const void *src_q[1] = {Q};
     void *dst_q[1] = {L.Qp};
@@ -259,12 +293,45 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
     void *dst_k[2] = {L.Kp, L.Vp};
     SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, 2, src_k, dst_k, dtype, d,
                             L.stage_ws, st));
+    profile_mark(pb, 3, st);
     // Section 4.2: which (query cluster, key cluster) pairs to compute
     SVG2_TRY(select_launch(cq_inout, ck_inout, L.counts_q, L.counts_k, H, Cq, Ck, d, top_p, L.row_ptr, L.col_idx,
                            nullptr, L.density, L.stage_ws, st));
+    profile_mark(pb, 4, st);
     // Section 4.3: attention over the selected pairs, result back in token order
-    return attn_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx,
-                       L.perm_q, 0.f, O, lse, L.stage_ws, st);
+    SVG2_TRY(attn_plan_launch(dtype, H, N, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx, L.stage_ws, st));
+    profile_mark(pb, 5, st);
+    SVG2_TRY(attn_main_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, 0.f, O, lse, L.stage_ws,
+                              st));
+    profile_mark(pb, 6, st);
+    return SVG2_OK;
+}
+
+int svg2_profile_enable(int enable)
+{
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.on = enable != 0;
+    return SVG2_OK;
+}
+
+int svg2_profile_read(float *stage_ms, int *n_calls)
+{
+    clear_error();
+    SVG2_REQUIRE(stage_ms && n_calls, SVG2_INVALID_ARG, "stage_ms and n_calls must be non-null");
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (int k = 0; k < SVG2_N_STAGES; ++k) stage_ms[k] = 0.f;
+    for (int c = 0; c < g_prof.ncalls; ++c) {
+        const int base = c * (SVG2_N_STAGES + 1);
+        SVG2_HIP_CHECK(hipEventSynchronize(g_prof.ev[base + SVG2_N_STAGES]));
+        for (int k = 0; k < SVG2_N_STAGES; ++k) {
+            float ms = 0.f;
+            SVG2_HIP_CHECK(hipEventElapsedTime(&ms, g_prof.ev[base + k], g_prof.ev[base + k + 1]));
+            stage_ms[k] += ms;
+        }
+    }
+    *n_calls = g_prof.ncalls;
+    g_prof.ncalls = 0;
+    return SVG2_OK;
 }
 
 }  // extern "C"

@@ -457,22 +457,47 @@ size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
     return c.used;
 }
 
-int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
-                const int32_t *offsets_q, const int32_t *offsets_k, const int32_t *row_ptr,
-                const int32_t *col_idx, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
-                hipStream_t st)
-{
-    const int BM = attn_bm(dtype);
-    const int max_tiles = cdiv(N, BM) + Cq;
-    Carver c(ws);
-    int4 *tiles = c.take<int4>((size_t)H * max_tiles);
-    int32_t *n_tiles = c.take<int32_t>((size_t)H);
-    int2 *runs = c.take<int2>((size_t)H * Cq * Ck);
-    int32_t *row_keys = c.take<int32_t>((size_t)H * Cq);
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)d);
+struct AttnWs {
+    int4 *tiles;
+    int32_t *n_tiles;
+    int2 *runs;
+    int32_t *row_keys;
+    int max_tiles;
+};
 
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(H), dim3(256), 0, st, offsets_q, offsets_k, row_ptr, col_idx, Cq, Ck, BM,
-                       max_tiles, tiles, n_tiles, runs, row_keys);
+static AttnWs attn_carve(void *ws, int dtype, int H, int N, int Cq, int Ck)
+{
+    AttnWs a;
+    a.max_tiles = cdiv(N, attn_bm(dtype)) + Cq;
+    Carver c(ws);
+    a.tiles = c.take<int4>((size_t)H * a.max_tiles);
+    a.n_tiles = c.take<int32_t>((size_t)H);
+    a.runs = c.take<int2>((size_t)H * Cq * Ck);
+    a.row_keys = c.take<int32_t>((size_t)H * Cq);
+    return a;
+}
+
+int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
+                     const int32_t *row_ptr, const int32_t *col_idx, void *ws, hipStream_t st)
+{
+    const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(H), dim3(256), 0, st, offsets_q, offsets_k, row_ptr, col_idx, Cq, Ck,
+                       attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys);
+    SVG2_HIP_CHECK(hipGetLastError());
+    return SVG2_OK;
+}
+
+int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
+                     const int32_t *row_ptr, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
+                     hipStream_t st)
+{
+    const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
+    const int max_tiles = a.max_tiles;
+    int4 *tiles = a.tiles;
+    int32_t *n_tiles = a.n_tiles;
+    int2 *runs = a.runs;
+    int32_t *row_keys = a.row_keys;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)d);
     if (dtype == SVG2_BF16) {
         const int total = H * max_tiles;
         const int nwg = cdiv(total, 8) * 8;
@@ -507,6 +532,16 @@ int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H
     }
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
+}
+
+int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
+                const int32_t *offsets_q, const int32_t *offsets_k, const int32_t *row_ptr,
+                const int32_t *col_idx, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
+                hipStream_t st)
+{
+    const int rc = attn_plan_launch(dtype, H, N, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, ws, st);
+    if (rc != SVG2_OK) return rc;
+    return attn_main_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, row_ptr, perm_q, scale, O, lse, ws, st);
 }
 
 }  // namespace svg2

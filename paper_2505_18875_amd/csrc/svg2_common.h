@@ -89,4 +89,11 @@ int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H
                 const int32_t *row_ptr, const int32_t *col_idx, const int32_t *perm_q, float scale,
                 void *O, float *lse, void *ws, hipStream_t st);
 
+// the two halves of attn_launch, separately (so a caller can time them)
+int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
+                     const int32_t *row_ptr, const int32_t *col_idx, void *ws, hipStream_t st);
+int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
+                     const int32_t *row_ptr, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
+                     hipStream_t st);
+
 }  // namespace svg2

@@ -7,10 +7,14 @@
 //             lane's 16 accumulators are 16 centroids of ONE token and the
 //             running argmin stays in registers.  dist = ||c||^2 - 2 x.c.
 //             fp32 input: a plain FMA kernel (one token per thread).
-//   update    LDS-privatised segmented sum: a workgroup owns a token range and
-//             a slice of the d columns, accumulates sum[label][col] in LDS
-//             with ds_add_f32, then writes its partial sums (no global
-//             atomics; the partials are reduced in a fixed order).
+//   update    segmented sum over the label-sorted token order: the counting sort
+//             of the permutation stage gives offsets and the sorted token ids;
+//             every cluster is cut into pieces of at most KM_SEG rows, one
+//             wavefront sums one piece in registers (4 rows of 256 bytes per
+//             load instruction) and writes a partial sum.  No atomics: the
+//             partials of a cluster are added in a fixed order, so the
+//             centroids are reproducible bit for bit, and the cost does not
+//             depend on how skewed the cluster sizes are.
 //   finalize  mean = sum / count (an empty cluster keeps its centroid), the
 //             bf16 copy of the centroids the next assign reads, and ||c||^2.
 //
@@ -26,13 +30,17 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 static constexpr int KM_CT = 128;      // centroids staged in LDS per step (bf16 kernel)
 static constexpr int KM_TB = 4;        // 32-token blocks per wavefront (bf16 kernel)
 static constexpr int KM_WG_TOKENS = 4 * KM_TB * 32;
+static constexpr int KM_UB = 4;        // load instructions in flight per wavefront in the segmented sum
+static constexpr int KM_SEG = 256;     // rows per piece of the segmented sum
 
 // ---------------------------------------------------------------- finalize
 // grid (C, H), block d.  do_update = 0: centroids <- init (first call).
+// Cluster j owns pieces first_piece[j] .. first_piece[j+1] of the head.
 template <bool BF16>
 __global__ void kmeans_finalize_kernel(const float *__restrict__ init, float *__restrict__ centroids,
-                                       const float *__restrict__ psum, const int32_t *__restrict__ pcnt,
-                                       int nchunks, int C, int d, bf16_t *__restrict__ cb, float *__restrict__ cn,
+                                       const float *__restrict__ psum, const int32_t *__restrict__ first_piece,
+                                       const int32_t *__restrict__ offsets, int max_pieces, int C, int d,
+                                       bf16_t *__restrict__ cb, float *__restrict__ cn,
                                        int32_t *__restrict__ counts_out, int do_update)
 {
     __shared__ float s_red[2];
@@ -40,11 +48,11 @@ __global__ void kmeans_finalize_kernel(const float *__restrict__ init, float *__
     const size_t idx = ((size_t)h * C + j) * d + k;
     float c;
     if (do_update) {
-        int cnt = 0;
-        for (int q = 0; q < nchunks; ++q) cnt += pcnt[((size_t)h * nchunks + q) * C + j];
+        const int cnt = offsets[(size_t)h * (C + 1) + j + 1] - offsets[(size_t)h * (C + 1) + j];
         if (cnt > 0) {
+            const int p0 = first_piece[(size_t)h * (C + 1) + j], p1 = first_piece[(size_t)h * (C + 1) + j + 1];
             float s = 0.f;
-            for (int q = 0; q < nchunks; ++q) s += psum[(((size_t)h * nchunks + q) * C + j) * d + k];
+            for (int q = p0; q < p1; ++q) s += psum[((size_t)h * max_pieces + q) * d + k];
             c = s / (float)cnt;
         } else {
             c = centroids[idx];
@@ -231,60 +239,106 @@ __global__ __launch_bounds__(128) void kmeans_assign_f32_kernel(const float *__r
 }
 
 // ---------------------------------------------------------------- update
-// grid (nchunks, D / DS, H), block 256.  A lane owns 4 consecutive columns of
-// a token; DS / 4 lanes cover the slice; 256 / (DS / 4) tokens are in flight,
-// each group of lanes walking its own contiguous sub-range of the chunk so
-// that simultaneously processed tokens are far apart (neighbouring video
-// tokens tend to share a label, which would serialise the LDS atomics).
-template <typename T, int D>
-__global__ __launch_bounds__(256) void kmeans_update_kernel(const T *__restrict__ X,
-                                                            const int32_t *__restrict__ labels, int N, int C, int DS,
-                                                            int chunk_tokens, int nchunks,
-                                                            float *__restrict__ psum, int32_t *__restrict__ pcnt)
+// Pieces of at most KM_SEG sorted rows, never crossing a cluster boundary.
+// grid (H), block 256.
+__global__ __launch_bounds__(256) void kmeans_pieces_kernel(const int32_t *__restrict__ offsets, int C,
+                                                            int max_pieces, int4 *__restrict__ pieces,
+                                                            int32_t *__restrict__ first_piece,
+                                                            int32_t *__restrict__ n_pieces)
 {
-    extern __shared__ __align__(16) float s_sum[];                 // [C * DS], then int counts [C]
-    int32_t *s_cnt = reinterpret_cast<int32_t *>(s_sum + (size_t)C * DS);
-    const int chunk = blockIdx.x, slice = blockIdx.y, h = blockIdx.z, tid = threadIdx.x;
-    for (int e = tid; e < C * DS; e += 256) s_sum[e] = 0.f;
-    for (int e = tid; e < C; e += 256) s_cnt[e] = 0;
+    __shared__ int32_t s_wave[4];
+    __shared__ int32_t s_carry;
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t *off = offsets + (size_t)h * (C + 1);
+    if (tid == 0) s_carry = 0;
     __syncthreads();
-    const int lpt = DS / 4;                       // lanes per token
-    const int groups = 256 / lpt;                 // tokens in flight
-    const int g = tid / lpt, part = tid % lpt;
-    const int n0 = chunk * chunk_tokens, n1 = min(N, n0 + chunk_tokens);
-    const int per = (n1 - n0 + groups - 1) / groups;
-    const int a = min(n1, n0 + g * per), b = min(n1, a + per);
-    const int col0 = slice * DS + part * 4;
-    const T *Xh = X + (size_t)h * N * D;
-    const int32_t *lab = labels + (size_t)h * N;
-    for (int n = a; n < b; ++n) {
-        const int l = lab[n];
-        const T *p = Xh + (size_t)n * D + col0;
-        float v0, v1, v2, v3;
-        if (sizeof(T) == 2) {
-            const uint2 w = *reinterpret_cast<const uint2 *>(p);
-            v0 = __uint_as_float(w.x << 16); v1 = __uint_as_float(w.x & 0xFFFF0000u);
-            v2 = __uint_as_float(w.y << 16); v3 = __uint_as_float(w.y & 0xFFFF0000u);
-        } else {
-            const float4 w = *reinterpret_cast<const float4 *>(p);
-            v0 = w.x; v1 = w.y; v2 = w.z; v3 = w.w;
+    for (int c0 = 0; c0 < C; c0 += 256) {
+        const int c = c0 + tid;
+        const int start = (c < C) ? off[c] : 0;
+        const int size = (c < C) ? off[c + 1] - start : 0;
+        const int np = (size + KM_SEG - 1) / KM_SEG;
+        int incl = np;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
         }
-        float *dst = s_sum + (size_t)l * DS + part * 4;
-        atomicAdd(dst + 0, v0);
-        atomicAdd(dst + 1, v1);
-        atomicAdd(dst + 2, v2);
-        atomicAdd(dst + 3, v3);
-        if (slice == 0 && part == 0) atomicAdd(&s_cnt[l], 1);
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int base = s_carry;
+        for (int w = 0; w < wave; ++w) base += s_wave[w];
+        const int first = base + incl - np;
+        if (c < C) first_piece[(size_t)h * (C + 1) + c] = first;
+        for (int t = 0; t < np; ++t)
+            pieces[(size_t)h * max_pieces + first + t] = make_int4(c, start + t * KM_SEG, min(KM_SEG, size - t * KM_SEG), 0);
+        __syncthreads();
+        if (tid == 255) s_carry = base + incl;
+        __syncthreads();
     }
-    __syncthreads();
-    float *out = psum + ((size_t)h * nchunks + chunk) * C * D;
-    for (int e = tid; e < C * DS; e += 256) {
-        const int c = e / DS, k = e % DS;
-        out[(size_t)c * D + slice * DS + k] = s_sum[e];
+    if (tid == 0) {
+        first_piece[(size_t)h * (C + 1) + C] = s_carry;
+        n_pieces[h] = s_carry;
     }
-    if (slice == 0) {
-        int32_t *oc = pcnt + ((size_t)h * nchunks + chunk) * C;
-        for (int e = tid; e < C; e += 256) oc[e] = s_cnt[e];
+}
+
+// grid (ceil(max_pieces / 4), H), block 256: one wavefront per piece.  A row is
+// LPR lanes of 16 bytes; 64 / LPR rows are read per instruction and KM_UB
+// instructions are in flight before their values are added.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kmeans_segsum_kernel(const T *__restrict__ X, const int32_t *__restrict__ perm,
+                                                            int N, int max_pieces, const int4 *__restrict__ pieces,
+                                                            const int32_t *__restrict__ n_pieces,
+                                                            float *__restrict__ psum)
+{
+    constexpr int EPL = 16 / sizeof(T);            // elements per lane
+    constexpr int LPR = D / EPL;                   // lanes per row
+    constexpr int RPI = 64 / LPR;                  // rows per instruction
+    const int h = blockIdx.y, lane = threadIdx.x & 63;
+    const int piece = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (piece >= n_pieces[h]) return;
+    const int4 desc = pieces[(size_t)h * max_pieces + piece];
+    const int row0 = desc.y, nrows = desc.z;
+    const int sub = lane / LPR, part = lane % LPR;
+    const T *Xh = X + (size_t)h * N * D;
+    const int32_t *pm = perm + (size_t)h * N;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int r = 0; r < nrows; r += RPI * KM_UB) {
+        uint4 v[KM_UB];
+        bool ok[KM_UB];
+#pragma unroll
+        for (int u = 0; u < KM_UB; ++u) {
+            const int rr = r + u * RPI + sub;
+            ok[u] = rr < nrows;
+            const int src = pm[row0 + min(rr, nrows - 1)];
+            v[u] = reinterpret_cast<const uint4 *>(Xh + (size_t)src * D)[part];
+        }
+#pragma unroll
+        for (int u = 0; u < KM_UB; ++u) {
+            if (!ok[u]) continue;
+            const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            if (sizeof(T) == 2) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[2 * q] += __uint_as_float(w[q] << 16);
+                    acc[2 * q + 1] += __uint_as_float(w[q] & 0xFFFF0000u);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += __uint_as_float(w[q]);
+            }
+        }
+    }
+    // lanes with the same `part` hold the same columns
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
+    if (sub == 0) {
+        float *out = psum + ((size_t)h * max_pieces + piece) * D + part * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+            *reinterpret_cast<float4 *>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
     }
 }
 
@@ -295,79 +349,81 @@ __global__ void kmeans_zero_kernel(float *p, int n)
 }
 
 // ---------------------------------------------------------------- host side
-struct KmeansPlan {
-    int DS, nslices, nchunks, chunk_tokens;
+struct KmeansWs {
+    bf16_t *cb;
+    float *cn;
+    int32_t *offsets, *perm, *first_piece, *n_pieces;
+    int4 *pieces;
+    float *psum;
+    void *sort_ws;
+    int max_pieces;
+    size_t total;
 };
 
-static KmeansPlan kmeans_plan(int H, int N, int d, int C)
+static KmeansWs kmeans_carve(void *ws, int H, int N, int d, int C)
 {
-    KmeansPlan p;
-    p.DS = 32;
-    while (p.DS > 4 && (size_t)C * p.DS * sizeof(float) > 64 * 1024) p.DS >>= 1;
-    p.nslices = d / p.DS;
-    int want = cdiv(1024, H * p.nslices);
-    int maxc = cdiv(N, 1024);
-    p.nchunks = want < 1 ? 1 : (want > maxc ? maxc : want);
-    p.chunk_tokens = cdiv(N, p.nchunks);
-    p.nchunks = cdiv(N, p.chunk_tokens);
-    return p;
+    KmeansWs k;
+    k.max_pieces = cdiv(N, KM_SEG) + C;
+    Carver c(ws);
+    k.cb = c.take<bf16_t>((size_t)H * C * d);
+    k.cn = c.take<float>((size_t)H * C);
+    k.offsets = c.take<int32_t>((size_t)H * (C + 1));
+    k.perm = c.take<int32_t>((size_t)H * N);
+    k.first_piece = c.take<int32_t>((size_t)H * (C + 1));
+    k.n_pieces = c.take<int32_t>((size_t)H);
+    k.pieces = c.take<int4>((size_t)H * k.max_pieces);
+    k.psum = c.take<float>((size_t)H * k.max_pieces * d);
+    k.sort_ws = c.take<char>(permute_ws_bytes(H, N, C));
+    k.total = c.used;
+    return k;
 }
 
 size_t kmeans_ws_bytes(int dtype, int H, int N, int d, int C)
 {
     (void)dtype;
-    const KmeansPlan p = kmeans_plan(H, N, d, C);
-    Carver c(nullptr);
-    c.take<bf16_t>((size_t)H * C * d);                       // bf16 centroids
-    c.take<float>((size_t)H * C);                            // ||c||^2
-    c.take<float>((size_t)H * p.nchunks * C * d);            // partial sums
-    c.take<int32_t>((size_t)H * p.nchunks * C);              // partial counts
-    return c.used;
+    return kmeans_carve(nullptr, H, N, d, C).total;
 }
 
 template <typename T, int D, bool BF16>
 static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *init, float *centroids,
-                       int32_t *labels, int32_t *counts, float *objective, void *ws, hipStream_t st)
+                      int32_t *labels, int32_t *counts, float *objective, void *ws, hipStream_t st)
 {
-    const KmeansPlan p = kmeans_plan(H, N, D, C);
-    Carver c(ws);
-    bf16_t *cb = c.take<bf16_t>((size_t)H * C * D);
-    float *cn = c.take<float>((size_t)H * C);
-    float *psum = c.take<float>((size_t)H * p.nchunks * C * D);
-    int32_t *pcnt = c.take<int32_t>((size_t)H * p.nchunks * C);
-
+    const KmeansWs k = kmeans_carve(ws, H, N, D, C);
     if (objective)
         hipLaunchKernelGGL(kmeans_zero_kernel, dim3(cdiv(H * iters, 256)), dim3(256), 0, st, objective, H * iters);
-    hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, init, centroids, psum, pcnt,
-                       p.nchunks, C, D, cb, cn, (int32_t *)nullptr, 0);
-    const size_t upd_lds = (size_t)C * p.DS * sizeof(float) + (size_t)C * sizeof(int32_t);
-    SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kmeans_update_kernel<T, D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)upd_lds));
+    hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, init, centroids, k.psum,
+                       k.first_piece, k.offsets, k.max_pieces, C, D, k.cb, k.cn, (int32_t *)nullptr, 0);
     for (int t = 0; t < iters; ++t) {
         float *obj = objective ? objective + t : nullptr;
         if (BF16) {
             const dim3 grid(cdiv(N, KM_WG_TOKENS), H);
             const bf16_t *Xb = reinterpret_cast<const bf16_t *>(X);
             if (obj)
-                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, true>), grid, dim3(256), 0, st, Xb, cb, cn, N, C,
+                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, true>), grid, dim3(256), 0, st, Xb, k.cb, k.cn, N, C,
                                    labels, obj, iters);
             else
-                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, false>), grid, dim3(256), 0, st, Xb, cb, cn, N, C,
+                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, false>), grid, dim3(256), 0, st, Xb, k.cb, k.cn, N, C,
                                    labels, obj, iters);
         } else {
             const dim3 grid(cdiv(N, 128), H);
             const float *Xf = reinterpret_cast<const float *>(X);
             if (obj)
-                hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, true>), grid, dim3(128), 0, st, Xf, centroids, cn, N,
+                hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, true>), grid, dim3(128), 0, st, Xf, centroids, k.cn, N,
                                    C, labels, obj, iters);
             else
-                hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, false>), grid, dim3(128), 0, st, Xf, centroids, cn, N,
+                hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, false>), grid, dim3(128), 0, st, Xf, centroids, k.cn, N,
                                    C, labels, obj, iters);
         }
-        hipLaunchKernelGGL((kmeans_update_kernel<T, D>), dim3(p.nchunks, p.nslices, H), dim3(256), upd_lds, st, X,
-                           labels, N, C, p.DS, p.chunk_tokens, p.nchunks, psum, pcnt);
+        // label-sorted order of the tokens, then the segmented sum over it
+        const int rc = permute_launch(labels, H, N, C, k.offsets, k.perm, nullptr, 0, nullptr, nullptr, 0, 0,
+                                      k.sort_ws, st);
+        if (rc != SVG2_OK) return rc;
+        hipLaunchKernelGGL(kmeans_pieces_kernel, dim3(H), dim3(256), 0, st, k.offsets, C, k.max_pieces, k.pieces,
+                           k.first_piece, k.n_pieces);
+        hipLaunchKernelGGL((kmeans_segsum_kernel<T, D>), dim3(cdiv(k.max_pieces, 4), H), dim3(256), 0, st, X, k.perm, N,
+                           k.max_pieces, k.pieces, k.n_pieces, k.psum);
         hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, (const float *)nullptr,
-                           centroids, psum, pcnt, p.nchunks, C, D, cb, cn, counts, 1);
+                           centroids, k.psum, k.first_piece, k.offsets, k.max_pieces, C, D, k.cb, k.cn, counts, 1);
     }
     return SVG2_OK;
 }
