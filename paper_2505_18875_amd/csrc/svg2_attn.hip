@@ -112,8 +112,19 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t *p)
         (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(const void *)p);
 }
 
+// Row of the permuted K / V that holds key number kk of the virtual key
+// sequence; `cur` is a cursor into the run table that only moves forward.
+__device__ __forceinline__ int run_lookup(const int2 *s_run, int &cur, int kk)
+{
+    int c = cur;
+    while (kk >= s_run[c + 1].y) ++c;
+    cur = c;
+    const int2 rs = s_run[c];
+    return rs.x + kk - rs.y;
+}
+
 template <int D, int QB>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int4 *__restrict__ tiles, const int32_t *__restrict__ n_tiles, int max_tiles,
@@ -122,11 +133,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(
 {
     constexpr int KS = D / 16;                 // k-steps of QK^T
     constexpr int DVB = D / 32;                // 32-row blocks of O^T
-    constexpr int ROW = D + 8;                 // LDS row stride (elements)
+    constexpr int ROW = D + 16;                // LDS row stride (elements): 4 consecutive rows start 8 banks apart
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
     constexpr int LPASS = 256 / CPR;           // rows loaded per pass
     constexpr int NPASS = ATT_BN / LPASS;      // passes per 64-key tile
-    constexpr int BM = 128 * QB;
 
     extern __shared__ __align__(16) unsigned char s_raw[];
     bf16_t *sK = reinterpret_cast<bf16_t *>(s_raw);                 // [2][64][ROW]
@@ -185,49 +195,44 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(
             for (int i = 0; i < 16; ++i) oacc[qb][b][i] = 0.f;
     }
 
-    // ---- loader state: this thread copies chunk `lchunk` of key slots lrow + p * LPASS
+    // ---- loader state: this thread copies chunk `lchunk` of key slots lrow + p * LPASS.
+    // The loads of one tile are spelled out per pass (ATT_FETCH) so that the
+    // staging registers and the run cursors stay in registers.
     const int lrow = tid / CPR, lchunk = tid % CPR;
-    int cur[NPASS];
-#pragma unroll
-    for (int p = 0; p < NPASS; ++p) cur[p] = 0;
-    uint4 kreg[NPASS], vreg[NPASS];
+    int cur0 = 0, cur1 = 0, cur2 = 0, cur3 = 0;
+    uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
+    kreg0 = kreg1 = kreg2 = kreg3 = vreg0 = vreg1 = vreg2 = vreg3 = make_uint4(0, 0, 0, 0);
     __syncthreads();                            // s_run visible
 
-    auto fetch = [&](int kt) {
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int kk = kt * ATT_BN + lrow + p * LPASS;
-            size_t src = 0;
-            if (kk < L) {
-                int c = cur[p];
-                while (kk >= s_run[c + 1].y) ++c;
-                cur[p] = c;
-                const int2 rs = s_run[c];
-                src = (size_t)(rs.x + kk - rs.y);
-            }
-            kreg[p] = reinterpret_cast<const uint4 *>(Kh + src * D)[lchunk];
-            vreg[p] = reinterpret_cast<const uint4 *>(Vh + src * D)[lchunk];
-        }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int off = buf * ATT_BN * ROW + (lrow + p * LPASS) * ROW + lchunk * 8;
-            *reinterpret_cast<uint4 *>(sK + off) = kreg[p];
-            *reinterpret_cast<uint4 *>(sV + off) = vreg[p];
-        }
-    };
+#define ATT_FETCH(P, KT)                                                                   \
+    if (P < NPASS) {                                                                       \
+        const int kk = (KT) * ATT_BN + lrow + P * LPASS;                                   \
+        size_t src = 0;                                                                    \
+        if (kk < L) {                                                                      \
+            src = (size_t)run_lookup(s_run, cur##P, kk);                                   \
+        }                                                                                  \
+        kreg##P = reinterpret_cast<const uint4 *>(Kh + src * D)[lchunk];                   \
+        vreg##P = reinterpret_cast<const uint4 *>(Vh + src * D)[lchunk];                   \
+    }
+#define ATT_STAGE(P, BUF)                                                                  \
+    if (P < NPASS) {                                                                       \
+        const int off = (BUF) * ATT_BN * ROW + (lrow + P * LPASS) * ROW + lchunk * 8;      \
+        *reinterpret_cast<uint4 *>(sK + off) = kreg##P;                                    \
+        *reinterpret_cast<uint4 *>(sV + off) = vreg##P;                                    \
+    }
+#define ATT_FETCH_ALL(KT) ATT_FETCH(0, KT) ATT_FETCH(1, KT) ATT_FETCH(2, KT) ATT_FETCH(3, KT)
+#define ATT_STAGE_ALL(BUF) ATT_STAGE(0, BUF) ATT_STAGE(1, BUF) ATT_STAGE(2, BUF) ATT_STAGE(3, BUF)
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
     if (ntile > 0) {
-        fetch(0);
-        stage(0);
+        ATT_FETCH_ALL(0)
+        ATT_STAGE_ALL(0)
     }
     __syncthreads();
 
     for (int kt = 0; kt < ntile; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < ntile) fetch(kt + 1);
+        if (kt + 1 < ntile) { ATT_FETCH_ALL(kt + 1) }
         if (wave_active) {
             const bf16_t *bK = sK + buf * ATT_BN * ROW;
             const bf16_t *bV = sV + buf * ATT_BN * ROW;
@@ -320,9 +325,14 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(
                 }
             }
         }
-        if (kt + 1 < ntile) stage(buf ^ 1);
+        if (kt + 1 < ntile) { ATT_STAGE_ALL(buf ^ 1) }
         __syncthreads();
     }
+
+#undef ATT_FETCH
+#undef ATT_STAGE
+#undef ATT_FETCH_ALL
+#undef ATT_STAGE_ALL
 
     // ---- epilogue: normalise, store at the original row
 #pragma unroll
@@ -505,7 +515,7 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
-        const size_t lds = (size_t)4 * ATT_BN * (d + 8) * sizeof(bf16_t) + (size_t)(Ck + 1) * sizeof(int2);
+        const size_t lds = (size_t)4 * ATT_BN * (d + 16) * sizeof(bf16_t) + (size_t)(Ck + 1) * sizeof(int2);
         if (d == 128) {
             auto kern = attn_bf16_kernel<128, ATT_QB>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
