@@ -133,15 +133,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 {
     constexpr int KS = D / 16;                 // k-steps of QK^T
     constexpr int DVB = D / 32;                // 32-row blocks of O^T
-    constexpr int ROW = D + 16;                // LDS row stride (elements): 4 consecutive rows start 8 banks apart
+    constexpr int ROWK = D + 8;                // LDS row strides (elements), chosen so that the 16 rows one
+    constexpr int ROWV = D + 32;               // b128 pass / the 4 rows one transposing pass touch differ in banks
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
     constexpr int LPASS = 256 / CPR;           // rows loaded per pass
     constexpr int NPASS = ATT_BN / LPASS;      // passes per 64-key tile
 
     extern __shared__ __align__(16) unsigned char s_raw[];
-    bf16_t *sK = reinterpret_cast<bf16_t *>(s_raw);                 // [2][64][ROW]
-    bf16_t *sV = sK + 2 * ATT_BN * ROW;                             // [2][64][ROW]
-    int2 *s_run = reinterpret_cast<int2 *>(sV + 2 * ATT_BN * ROW);  // [nnz + 1]
+    bf16_t *sK = reinterpret_cast<bf16_t *>(s_raw);                 // [2][64][ROWK]
+    bf16_t *sV = sK + 2 * ATT_BN * ROWK;                            // [2][64][ROWV]
+    int32_t *s_rows = reinterpret_cast<int32_t *>(sV + 2 * ATT_BN * ROWV);   // [2][64]
+    int2 *s_run = reinterpret_cast<int2 *>(s_rows + 2 * ATT_BN);    // [nnz + 1]
 
     // ---- which work item: consecutive workgroup ids go round-robin over the
     // 8 XCDs; give every XCD a contiguous range of (head, tile) so the tiles
@@ -195,35 +197,43 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
             for (int i = 0; i < 16; ++i) oacc[qb][b][i] = 0.f;
     }
 
-    // ---- loader state: this thread copies chunk `lchunk` of key slots lrow + p * LPASS.
-    // The loads of one tile are spelled out per pass (ATT_FETCH) so that the
-    // staging registers and the run cursors stay in registers.
+    // ---- loader.  The permuted K / V row of every key slot of a tile is looked up
+    // by ONE wavefront (wave kt % 4, lane = slot) two tiles ahead and parked in
+    // s_rows; every thread then copies chunk `lchunk` of slots lrow * NPASS + p.
+    // The per-pass code is spelled out (ATT_FETCH) so the staging registers stay
+    // in registers.
     const int lrow = tid / CPR, lchunk = tid % CPR;
-    int cur0 = 0, cur1 = 0, cur2 = 0, cur3 = 0;
+    const char *Kb = reinterpret_cast<const char *>(Kh);
+    const char *Vb = reinterpret_cast<const char *>(Vh);
+    int cur = 0;
     uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
     kreg0 = kreg1 = kreg2 = kreg3 = vreg0 = vreg1 = vreg2 = vreg3 = make_uint4(0, 0, 0, 0);
     __syncthreads();                            // s_run visible
 
+#define ATT_ROWS(KT)                                                                       \
+    if (wave == ((KT) & 3)) {                                                              \
+        const int kk = (KT) * ATT_BN + lane;                                               \
+        s_rows[((KT) & 1) * ATT_BN + lane] = (kk < L) ? run_lookup(s_run, cur, kk) : 0;    \
+    }
 #define ATT_FETCH(P, KT)                                                                   \
     if (P < NPASS) {                                                                       \
-        const int kk = (KT) * ATT_BN + lrow + P * LPASS;                                   \
-        size_t src = 0;                                                                    \
-        if (kk < L) {                                                                      \
-            src = (size_t)run_lookup(s_run, cur##P, kk);                                   \
-        }                                                                                  \
-        kreg##P = reinterpret_cast<const uint4 *>(Kh + src * D)[lchunk];                   \
-        vreg##P = reinterpret_cast<const uint4 *>(Vh + src * D)[lchunk];                   \
+        const unsigned off = (unsigned)s_rows[((KT) & 1) * ATT_BN + lrow * NPASS + P] * (unsigned)(D * 2) + lchunk * 16; \
+        kreg##P = *reinterpret_cast<const uint4 *>(Kb + off);                              \
+        vreg##P = *reinterpret_cast<const uint4 *>(Vb + off);                              \
     }
 #define ATT_STAGE(P, BUF)                                                                  \
     if (P < NPASS) {                                                                       \
-        const int off = (BUF) * ATT_BN * ROW + (lrow + P * LPASS) * ROW + lchunk * 8;      \
-        *reinterpret_cast<uint4 *>(sK + off) = kreg##P;                                    \
-        *reinterpret_cast<uint4 *>(sV + off) = vreg##P;                                    \
+        const int r_ = (BUF) * ATT_BN + lrow * NPASS + P;                                  \
+        *reinterpret_cast<uint4 *>(sK + r_ * ROWK + lchunk * 8) = kreg##P;                 \
+        *reinterpret_cast<uint4 *>(sV + r_ * ROWV + lchunk * 8) = vreg##P;                 \
     }
 #define ATT_FETCH_ALL(KT) ATT_FETCH(0, KT) ATT_FETCH(1, KT) ATT_FETCH(2, KT) ATT_FETCH(3, KT)
 #define ATT_STAGE_ALL(BUF) ATT_STAGE(0, BUF) ATT_STAGE(1, BUF) ATT_STAGE(2, BUF) ATT_STAGE(3, BUF)
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
+    ATT_ROWS(0)
+    ATT_ROWS(1)
+    __syncthreads();
     if (ntile > 0) {
         ATT_FETCH_ALL(0)
         ATT_STAGE_ALL(0)
@@ -233,9 +243,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     for (int kt = 0; kt < ntile; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < ntile) { ATT_FETCH_ALL(kt + 1) }
+        if (kt + 2 < ntile) { ATT_ROWS(kt + 2) }
         if (wave_active) {
-            const bf16_t *bK = sK + buf * ATT_BN * ROW;
-            const bf16_t *bV = sV + buf * ATT_BN * ROW;
+            const bf16_t *bK = sK + buf * ATT_BN * ROWK;
+            const bf16_t *bV = sV + buf * ATT_BN * ROWV;
             // ---- S^T block: rows = 64 keys (2 blocks of 32), columns = queries
             f32x16 sacc[2][QB];
 #pragma unroll
@@ -249,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
                     bf16x8 a;
-                    const uint4 w = *reinterpret_cast<const uint4 *>(bK + (kb * 32 + col) * ROW + 16 * s + 8 * half);
+                    const uint4 w = *reinterpret_cast<const uint4 *>(bK + (kb * 32 + col) * ROWK + 16 * s + 8 * half);
                     __builtin_memcpy(&a, &w, 16);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
@@ -279,8 +290,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 #pragma unroll
                     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][qb][i]);
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[qb], mx * scale_log2);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+                // the running maximum only moves when it would grow by more than 2^8: the
+                // probabilities stay below 256 (fine in bf16 / fp32) and most tiles skip
+                // the rescaling of the output accumulators
+                const float mx_s = mx * scale_log2;
+                const bool upd = mx_s > m_run[qb] + 8.0f;
+                const float m_new = upd ? mx_s : m_run[qb];
+                if (__any(upd)) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+                    l_run[qb] *= alpha;
+#pragma unroll
+                    for (int b = 0; b < DVB; ++b)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[qb][b][i] *= alpha;
+                }
                 m_run[qb] = m_new;
                 float psum = 0.f;
 #pragma unroll
@@ -298,13 +321,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
                         for (int j = 0; j < 8; ++j) pk[j] = (__bf16)p[j];
                         pb[qb][kb * 2 + g] = pk;
                     }
-                l_run[qb] = fmaf(l_run[qb], alpha, psum);
-                if (__any(alpha != 1.0f)) {
-#pragma unroll
-                    for (int b = 0; b < DVB; ++b)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[qb][b][i] *= alpha;
-                }
+                l_run[qb] += psum;
             }
             // ---- O^T += V^T P^T
 #pragma unroll
@@ -314,8 +331,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
                     const int r16 = lane & 15;
                     const int dv = b * 32 + ((lane >> 4) & 1) * 16 + 4 * (r16 & 3);
                     const int key0 = ks * 16 + 4 * half + (r16 >> 2);
-                    const s16x4 lo = lds_read_tr16(bV + key0 * ROW + dv);
-                    const s16x4 hi = lds_read_tr16(bV + (key0 + 8) * ROW + dv);
+                    const s16x4 lo = lds_read_tr16(bV + key0 * ROWV + dv);
+                    const s16x4 hi = lds_read_tr16(bV + (key0 + 8) * ROWV + dv);
                     bf16x8 a;
                     __builtin_memcpy(&a, &lo, 8);
                     __builtin_memcpy(reinterpret_cast<char *>(&a) + 8, &hi, 8);
@@ -329,6 +346,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
         __syncthreads();
     }
 
+#undef ATT_ROWS
 #undef ATT_FETCH
 #undef ATT_STAGE
 #undef ATT_FETCH_ALL
@@ -515,7 +533,8 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
-        const size_t lds = (size_t)4 * ATT_BN * (d + 16) * sizeof(bf16_t) + (size_t)(Ck + 1) * sizeof(int2);
+        const size_t lds = (size_t)2 * ATT_BN * (2 * d + 40) * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
+                           (size_t)(Ck + 1) * sizeof(int2);
         if (d == 128) {
             auto kern = attn_bf16_kernel<128, ATT_QB>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
