@@ -32,6 +32,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 static constexpr int ATT_BN = 64;          // keys per tile
+static constexpr int ATT_GROUP = 8;        // consecutive tiles handed to one XCD
 
 // ---------------------------------------------------------------- plan
 // grid (H), block 256.
@@ -102,6 +103,35 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
     }
 }
 
+// tile_base[h] = number of tiles of heads < h; tile_base[H] = all tiles.  One workgroup.
+__global__ __launch_bounds__(256) void attn_tile_base_kernel(const int32_t *__restrict__ n_tiles, int H,
+                                                             int32_t *__restrict__ tile_base)
+{
+    __shared__ int32_t s_wave[4];
+    __shared__ int32_t s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int h0 = 0; h0 < H; h0 += 256) {
+        const int h = h0 + tid;
+        const int n = (h < H) ? n_tiles[h] : 0;
+        int incl = n;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int base = s_carry;
+        for (int w = 0; w < wave; ++w) base += s_wave[w];
+        if (h < H) tile_base[h] = base + incl - n;
+        __syncthreads();
+        if (tid == 255) s_carry = base + incl;
+        __syncthreads();
+    }
+    if (tid == 0) tile_base[H] = s_carry;
+}
+
 // ---------------------------------------------------------------- bf16 MFMA kernel
 // LDS transposing read: the 16 lanes of a block each pass the address of 4
 // consecutive 16-bit values (row r = lane % 16); lane L gets element L % 4 of
@@ -127,7 +157,7 @@ template <int D, int QB>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
-    const int4 *__restrict__ tiles, const int32_t *__restrict__ n_tiles, int max_tiles,
+    const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base, int max_tiles,
     const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2,
     bf16_t *__restrict__ O, float *__restrict__ lse)
 {
@@ -145,15 +175,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     int32_t *s_rows = reinterpret_cast<int32_t *>(sV + 2 * ATT_BN * ROWV);   // [2][64]
     int2 *s_run = reinterpret_cast<int2 *>(s_rows + 2 * ATT_BN);    // [nnz + 1]
 
-    // ---- which work item: consecutive workgroup ids go round-robin over the
-    // 8 XCDs; give every XCD a contiguous range of (head, tile) so the tiles
-    // that share keys also share an L2.
-    const int total = H * max_tiles;
-    const int per_xcd = gridDim.x / 8;
-    const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (v >= total) return;
-    const int h = v / max_tiles, t = v % max_tiles;
-    if (t >= n_tiles[h]) return;
+    // ---- which work item.  All tiles of all heads form one list (head-major, so
+    // neighbours share keys).  Consecutive workgroup ids go round-robin over the 8
+    // XCDs, each with its own L2: hand out the list in groups of ATT_GROUP
+    // consecutive tiles per XCD, so tiles that share keys share an L2 and every XCD
+    // gets the same amount of work whatever the per-head densities are.
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int v = (slot / ATT_GROUP) * (8 * ATT_GROUP) + xcd * ATT_GROUP + slot % ATT_GROUP;
+    if (v >= tile_base[H]) return;
+    int h = 0;
+    for (int step = 1 << 15; step > 0; step >>= 1)
+        if (h + step < H && tile_base[h + step] <= v) h += step;
+    const int t = v - tile_base[h];
     const int4 desc = tiles[(size_t)h * max_tiles + t];
     const int ci = desc.x, row0 = desc.y, nrows = desc.z;
 
@@ -240,6 +273,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     }
     __syncthreads();
 
+    // all global loads issued so far (queries, first tile) have landed: inside the loop
+    // the only loads in flight are the prefetch of the next tile, which nothing in the
+    // compute part has to wait for
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
     for (int kt = 0; kt < ntile; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < ntile) { ATT_FETCH_ALL(kt + 1) }
@@ -480,6 +517,7 @@ size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
     Carver c(nullptr);
     c.take<int4>((size_t)H * max_tiles);
     c.take<int32_t>((size_t)H);
+    c.take<int32_t>((size_t)H + 1);
     c.take<int2>((size_t)H * Cq * Ck);
     c.take<int32_t>((size_t)H * Cq);
     return c.used;
@@ -487,7 +525,7 @@ size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
 
 struct AttnWs {
     int4 *tiles;
-    int32_t *n_tiles;
+    int32_t *n_tiles, *tile_base;
     int2 *runs;
     int32_t *row_keys;
     int max_tiles;
@@ -500,6 +538,7 @@ static AttnWs attn_carve(void *ws, int dtype, int H, int N, int Cq, int Ck)
     Carver c(ws);
     a.tiles = c.take<int4>((size_t)H * a.max_tiles);
     a.n_tiles = c.take<int32_t>((size_t)H);
+    a.tile_base = c.take<int32_t>((size_t)H + 1);
     a.runs = c.take<int2>((size_t)H * Cq * Ck);
     a.row_keys = c.take<int32_t>((size_t)H * Cq);
     return a;
@@ -511,6 +550,7 @@ int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *off
     const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(H), dim3(256), 0, st, offsets_q, offsets_k, row_ptr, col_idx, Cq, Ck,
                        attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys);
+    hipLaunchKernelGGL(attn_tile_base_kernel, dim3(1), dim3(256), 0, st, a.n_tiles, H, a.tile_base);
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
 }
@@ -523,12 +563,13 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
     const int max_tiles = a.max_tiles;
     int4 *tiles = a.tiles;
     int32_t *n_tiles = a.n_tiles;
+    int32_t *tile_base = a.tile_base;
     int2 *runs = a.runs;
     int32_t *row_keys = a.row_keys;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)d);
     if (dtype == SVG2_BF16) {
         const int total = H * max_tiles;
-        const int nwg = cdiv(total, 8) * 8;
+        const int nwg = cdiv(total, 8 * ATT_GROUP) * 8 * ATT_GROUP;
         const float scale_log2 = scale * 1.4426950408889634f;
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
@@ -540,13 +581,13 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               n_tiles, max_tiles, runs, row_keys, scale_log2, o, lse);
+                               tile_base, max_tiles, runs, row_keys, scale_log2, o, lse);
         } else {
             auto kern = attn_bf16_kernel<64, ATT_QB>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               n_tiles, max_tiles, runs, row_keys, scale_log2, o, lse);
+                               tile_base, max_tiles, runs, row_keys, scale_log2, o, lse);
         }
     } else {
         const float *q = static_cast<const float *>(Qp), *k = static_cast<const float *>(Kp),
