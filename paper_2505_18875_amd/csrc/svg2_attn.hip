@@ -22,6 +22,8 @@
 //
 // The result of sorted row r is stored at row perm_q[r] (Section 4.1: the
 // inverse query permutation restores the original order).
+#include <type_traits>
+
 #include "svg2_common.h"
 
 namespace svg2 {
@@ -136,10 +138,18 @@ __global__ __launch_bounds__(256) void attn_tile_base_kernel(const int32_t *__re
 // LDS transposing read: the 16 lanes of a block each pass the address of 4
 // consecutive 16-bit values (row r = lane % 16); lane L gets element L % 4 of
 // rows L / 4, L / 4 + 4, L / 4 + 8, L / 4 + 12.
-__device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t *p)
+typedef __attribute__((address_space(3))) unsigned char lds_u8;      // byte in LDS (32-bit address)
+
+__device__ __forceinline__ s16x4 lds_read_tr16(const lds_u8 *p)
 {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(const void *)p);
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+}
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ u32x4 lds_read_b128(const lds_u8 *p)
+{
+    return *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(p);
 }
 
 // Row of the permuted K / V that holds key number kk of the virtual key
@@ -153,7 +163,38 @@ __device__ __forceinline__ int run_lookup(const int2 *s_run, int &cur, int kk)
     return rs.x + kk - rs.y;
 }
 
-template <int D, int QB>
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+// two floats -> two bf16 (round to nearest even) in one word, low half first
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
+{
+    const f32x2 f = {a, b};
+    const bf16x2 h = __builtin_convertvector(f, bf16x2);
+    unsigned w;
+    __builtin_memcpy(&w, &h, 4);
+    return w;
+}
+
+// acc + both bf16 halves of w (v_dot2c_f32_bf16 with a vector of ones): the row sum is taken
+// over the rounded probabilities, the same values the matrix cores multiply with V
+__device__ __forceinline__ float add_bf16x2(unsigned w, float acc)
+{
+    bf16x2 x;
+    __builtin_memcpy(&x, &w, 4);
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(x, ones, acc, false);
+}
+
+// words 4 k .. 4 k + 3 of the packed probabilities as an MFMA operand
+__device__ __forceinline__ bf16x8 pb_operand(const unsigned *pw, int k)
+{
+    bf16x8 r;
+    __builtin_memcpy(&r, pw + 4 * k, 16);
+    return r;
+}
+
+template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
@@ -163,16 +204,21 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 {
     constexpr int KS = D / 16;                 // k-steps of QK^T
     constexpr int DVB = D / 32;                // 32-row blocks of O^T
-    constexpr int ROWK = D + 8;                // LDS row strides (elements), chosen so that the 16 rows one
-    constexpr int ROWV = D + 32;               // b128 pass / the 4 rows one transposing pass touch differ in banks
+    constexpr int RB = 2 * D;                  // bytes per K / V row
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
-    constexpr int LPASS = 256 / CPR;           // rows loaded per pass
-    constexpr int NPASS = ATT_BN / LPASS;      // passes per 64-key tile
+    constexpr int RPI = 1024 / RB;             // rows one direct-to-LDS load instruction fills (64 lanes x 16 B)
+    constexpr int NPASS = ATT_BN / (4 * RPI);  // such instructions per wavefront, tile and tensor
+    constexpr int TILE_B = ATT_BN * RB;        // bytes of one K or V tile in LDS
 
+    // LDS: K tiles [2][64][D] and V tiles [2][64][D], rows unpadded (the direct loads
+    // fill 1024 contiguous bytes per instruction); bank conflicts are avoided by
+    // storing 16-byte chunk c of row r at position c ^ swz(r):
+    //   K  swz = (r / (256 / RB)) % CPR        the 16 rows of one ds_read_b128 pass differ
+    //   V  swz = 4 * ((r / (256 / RB)) % (CPR / 4))   the 4 rows of one transposing pass differ
     extern __shared__ __align__(16) unsigned char s_raw[];
-    bf16_t *sK = reinterpret_cast<bf16_t *>(s_raw);                 // [2][64][ROWK]
-    bf16_t *sV = sK + 2 * ATT_BN * ROWK;                            // [2][64][ROWV]
-    int32_t *s_rows = reinterpret_cast<int32_t *>(sV + 2 * ATT_BN * ROWV);   // [2][64]
+    unsigned char *sK = s_raw;                                      // [2][TILE_B]
+    unsigned char *sV = s_raw + 2 * TILE_B;                         // [2][TILE_B]
+    int32_t *s_rows = reinterpret_cast<int32_t *>(s_raw + 4 * TILE_B);   // [2][64]
     int2 *s_run = reinterpret_cast<int2 *>(s_rows + 2 * ATT_BN);    // [nnz + 1]
 
     // ---- which work item.  All tiles of all heads form one list (head-major, so
@@ -190,7 +236,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const int4 desc = tiles[(size_t)h * max_tiles + t];
     const int ci = desc.x, row0 = desc.y, nrows = desc.z;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront-uniform: lives in a scalar register
     const int half = lane >> 5, col = lane & 31;
 
     const int e0 = row_ptr[(size_t)h * (Cq + 1) + ci];
@@ -204,43 +251,39 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *Kh = K + (size_t)h * N * D;
     const bf16_t *Vh = V + (size_t)h * N * D;
 
-    // ---- queries as the B operand of S^T = K Q^T
-    bf16x8 qreg[QB][KS];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int r = row0 + min(nrows - 1, (wave * QB + qb) * 32 + col);
+    // ---- queries as the B operand of S^T = K Q^T: this wavefront owns 32 rows of the tile
+    bf16x8 qreg[KS];
+    {
+        const int r = row0 + min(nrows - 1, wave * 32 + col);
         const uint4 *src = reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + 8 * half);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const uint4 w = src[2 * s];
-            __builtin_memcpy(&qreg[qb][s], &w, 16);
+            __builtin_memcpy(&qreg[s], &w, 16);
         }
     }
-    const bool wave_active = (wave * QB) * 32 < nrows;
+    const bool wave_active = wave * 32 < nrows;
 
-    f32x16 oacc[QB][DVB];
-    float m_run[QB], l_run[QB];
+    f32x16 oacc[DVB];
+    float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
+    for (int b = 0; b < DVB; ++b)
 #pragma unroll
-        for (int b = 0; b < DVB; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[qb][b][i] = 0.f;
-    }
+        for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
 
-    // ---- loader.  The permuted K / V row of every key slot of a tile is looked up
-    // by ONE wavefront (wave kt % 4, lane = slot) two tiles ahead and parked in
-    // s_rows; every thread then copies chunk `lchunk` of slots lrow * NPASS + p.
-    // The per-pass code is spelled out (ATT_FETCH) so the staging registers stay
-    // in registers.
-    const int lrow = tid / CPR, lchunk = tid % CPR;
+    // ---- loader.  The permuted K / V row of every key slot of a tile is looked up by
+    // ONE wavefront (wave kt % 4, lane = slot) two tiles ahead and parked in s_rows.
+    // The rows then go from global memory straight into LDS (no staging registers):
+    // load instruction (wave, p) fills LDS rows (4 p + wave) * RPI .. + RPI of the tile,
+    // lane l the chunk position l % CPR of row l / CPR, so it fetches the global chunk
+    // that the swizzle puts there.
     const char *Kb = reinterpret_cast<const char *>(Kh);
     const char *Vb = reinterpret_cast<const char *>(Vh);
     int cur = 0;
-    uint4 kreg0, kreg1, kreg2, kreg3, vreg0, vreg1, vreg2, vreg3;
-    kreg0 = kreg1 = kreg2 = kreg3 = vreg0 = vreg1 = vreg2 = vreg3 = make_uint4(0, 0, 0, 0);
+    const int ld_row = lane / CPR;                                  // row inside the instruction's group
+    const int ld_swz = ((wave * RPI + ld_row) / (256 / RB));
+    const unsigned ld_koff = (unsigned)(((lane % CPR) ^ (ld_swz % CPR)) * 16);
+    const unsigned ld_voff = (unsigned)(((lane % CPR) ^ (4 * (ld_swz % (CPR / 4)))) * 16);
     __syncthreads();                            // s_run visible
 
 #define ATT_ROWS(KT)                                                                       \
@@ -248,169 +291,237 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
         const int kk = (KT) * ATT_BN + lane;                                               \
         s_rows[((KT) & 1) * ATT_BN + lane] = (kk < L) ? run_lookup(s_run, cur, kk) : 0;    \
     }
-#define ATT_FETCH(P, KT)                                                                   \
+#define ATT_FETCH(P, KT, BUF)                                                              \
     if (P < NPASS) {                                                                       \
-        const unsigned off = (unsigned)s_rows[((KT) & 1) * ATT_BN + lrow * NPASS + P] * (unsigned)(D * 2) + lchunk * 16; \
-        kreg##P = *reinterpret_cast<const uint4 *>(Kb + off);                              \
-        vreg##P = *reinterpret_cast<const uint4 *>(Vb + off);                              \
+        const int grp_ = (4 * P + wave) * RPI;                                             \
+        const unsigned off_ = (unsigned)s_rows[((KT) & 1) * ATT_BN + grp_ + ld_row] * (unsigned)RB;        \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Kb + (off_ + ld_koff)), \
+                                         (__attribute__((address_space(3))) void *)(sK + (BUF) * TILE_B + grp_ * RB), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Vb + (off_ + ld_voff)), \
+                                         (__attribute__((address_space(3))) void *)(sV + (BUF) * TILE_B + grp_ * RB), 16, 0, 0); \
     }
-#define ATT_STAGE(P, BUF)                                                                  \
-    if (P < NPASS) {                                                                       \
-        const int r_ = (BUF) * ATT_BN + lrow * NPASS + P;                                  \
-        *reinterpret_cast<uint4 *>(sK + r_ * ROWK + lchunk * 8) = kreg##P;                 \
-        *reinterpret_cast<uint4 *>(sV + r_ * ROWV + lchunk * 8) = vreg##P;                 \
+// Online-softmax bookkeeping for one block of 32 scores per query (16 per lane, the
+// other 16 in lane ^ 32).  The running maximum only moves when it would grow by
+// more than 2^8, so probabilities stay below 256 and the rescaling of the output
+// accumulators is rare.  FIX_PB: block 0's probabilities (pw[0..7]) are already
+// computed but not yet accumulated, so they are rescaled too.
+#define ATT_NEW_MAX(S, FIX_PB)                                                             \
+    {                                                                                      \
+        float mx = fmaxf(fmaxf(S[0], S[1]), S[2]);                                         \
+        _Pragma("unroll") for (int i = 3; i < 16; ++i) mx = fmaxf(mx, S[i]);               \
+        mx = fmaxf(mx, __shfl_xor(mx, 32));                                                \
+        const float mx_s = mx * scale_log2;                                                \
+        const bool upd = mx_s > m_run + 8.0f;                                              \
+        if (__any(upd)) {                                                                  \
+            const float m_new = upd ? mx_s : m_run;                                        \
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);                     \
+            m_run = m_new;                                                                 \
+            l_run *= alpha;                                                                \
+            _Pragma("unroll") for (int b = 0; b < DVB; ++b)                                \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;        \
+            if (FIX_PB) {                                                                  \
+                _Pragma("unroll") for (int j = 0; j < 8; ++j)                              \
+                    pw[j] = pack_bf16x2(__uint_as_float(pw[j] << 16) * alpha,              \
+                                        __uint_as_float(pw[j] & 0xFFFF0000u) * alpha);     \
+            }                                                                              \
+        }                                                                                  \
     }
-#define ATT_FETCH_ALL(KT) ATT_FETCH(0, KT) ATT_FETCH(1, KT) ATT_FETCH(2, KT) ATT_FETCH(3, KT)
-#define ATT_STAGE_ALL(BUF) ATT_STAGE(0, BUF) ATT_STAGE(1, BUF) ATT_STAGE(2, BUF) ATT_STAGE(3, BUF)
+#define ATT_FETCH_ALL(KT, BUF) ATT_FETCH(0, KT, BUF) ATT_FETCH(1, KT, BUF) ATT_FETCH(2, KT, BUF) ATT_FETCH(3, KT, BUF)
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
     ATT_ROWS(0)
     ATT_ROWS(1)
     __syncthreads();
-    if (ntile > 0) {
-        ATT_FETCH_ALL(0)
-        ATT_STAGE_ALL(0)
+    if (ntile > 0) { ATT_FETCH_ALL(0, 0) }
+    // per-lane LDS read offsets (bytes, buffer 0): K operand of k-step s, V^T operand of column block b
+    int koff[KS], voff[DVB];
+    {
+        const int kz = (col / (256 / RB)) % CPR;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) koff[s] = col * RB + (((2 * s + half) ^ kz) * 16);
+        const int r16 = lane & 15;
+        const int kr0 = 4 * half + (r16 >> 2);
+        const int vz = 4 * ((kr0 / (256 / RB)) % (CPR / 4));
+        const int cl = 2 * ((lane >> 4) & 1) + ((r16 & 3) >> 1);
+#pragma unroll
+        for (int b = 0; b < DVB; ++b) voff[b] = kr0 * RB + ((((4 * b) ^ vz) + cl) * 16) + (r16 & 1) * 8;
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): queries and the first tile have landed
     __syncthreads();
 
-    // all global loads issued so far (queries, first tile) have landed: inside the loop
-    // the only loads in flight are the prefetch of the next tile, which nothing in the
-    // compute part has to wait for
-    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
-    for (int kt = 0; kt < ntile; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < ntile) { ATT_FETCH_ALL(kt + 1) }
-        if (kt + 2 < ntile) { ATT_ROWS(kt + 2) }
-        if (wave_active) {
-            const bf16_t *bK = sK + buf * ATT_BN * ROWK;
-            const bf16_t *bV = sV + buf * ATT_BN * ROWV;
-            // ---- S^T block: rows = 64 keys (2 blocks of 32), columns = queries
-            f32x16 sacc[2][QB];
+    // One 64-key tile of this wavefront's 32 queries, from LDS buffer `buf`.  RAGGED: keys
+    // past `rem` do not exist (end of the key sequence) and get a score of -inf.
+    //
+    // The tile is two blocks of 32 keys, each with its own online-softmax step, and the
+    // instruction stream is laid out by hand (ATT_FENCE keeps the compiler from moving
+    // code across chunk boundaries): every matrix instruction of the second score block
+    // is followed by the vector work (exp2, row sum, bf16 packing) of 16 / KS scores of
+    // the first block, and every matrix instruction that accumulates the first block
+    // into the output by the vector work of the second block.  One matrix instruction
+    // keeps the cores busy for 32 cycles, about what 7 vector instructions take.
+    // Accumulator i of a block is key 8 (i/4) + 4 half + i%4 of that block.
+#define ATT_FENCE __builtin_amdgcn_sched_barrier(0);
+    auto compute_tile = [&](auto ragged_tag, auto buf_tag, int rem) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        constexpr int BUF = decltype(buf_tag)::value;
+        constexpr int EPC = 16 / KS;               // scores handled per chunk of score-block work
+        constexpr int NPV = 2 * DVB;               // matrix instructions per block in O^T += V^T P^T
+        constexpr int EPV = 16 / NPV;              // scores handled per chunk there
+        // LDS addresses are a per-lane 32-bit base plus a compile-time constant, which the
+        // DS instructions take as their immediate offset
+        const lds_u8 *lds = (const lds_u8 *)s_raw;
+        constexpr int KB = BUF * TILE_B, VB = 2 * TILE_B + BUF * TILE_B;
+        // V^T operand of matrix instruction idx (ks = idx / DVB: 16 keys, b = idx % DVB: 32 output columns)
+        auto load_v = [&](int idx) {
+            const int ks = idx / DVB, b = idx % DVB;
+            const s16x4 lo = lds_read_tr16((lds + voff[b]) + (VB + (ks * 16) * RB));
+            const s16x4 hi = lds_read_tr16((lds + voff[b]) + (VB + (ks * 16 + 8) * RB));
+            bf16x8 a;
+            __builtin_memcpy(&a, &lo, 8);
+            __builtin_memcpy(reinterpret_cast<char *>(&a) + 8, &hi, 8);
+            return a;
+        };
+        f32x16 s0, s1;
+        unsigned pw[16];                            // probabilities, two bf16 per word; 4 words = one B operand
+        bf16x8 ka[KS];
+        // ---- scores of block 0
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sacc[kb][qb][i] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    bf16x8 a;
-                    const uint4 w = *reinterpret_cast<const uint4 *>(bK + (kb * 32 + col) * ROWK + 16 * s + 8 * half);
-                    __builtin_memcpy(&a, &w, 16);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][s], sacc[kb][qb], 0, 0, 0);
-                }
-            }
-            // ---- ragged end of the key sequence
-            if (kt == ntile - 1 && (L % ATT_BN) != 0) {
-                const int rem = L - kt * ATT_BN;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = kb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                        if (key >= rem)
-#pragma unroll
-                            for (int qb = 0; qb < QB; ++qb) sacc[kb][qb][i] = -INFINITY;
-                    }
-            }
-            // ---- online softmax; accumulator i of block kb is key kb*32 + 8 (i/4) + 4 half + i%4
-            bf16x8 pb[QB][4];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float mx = sacc[0][qb][0];
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][qb][i]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // the running maximum only moves when it would grow by more than 2^8: the
-                // probabilities stay below 256 (fine in bf16 / fp32) and most tiles skip
-                // the rescaling of the output accumulators
-                const float mx_s = mx * scale_log2;
-                const bool upd = mx_s > m_run[qb] + 8.0f;
-                const float m_new = upd ? mx_s : m_run[qb];
-                if (__any(upd)) {
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-                    l_run[qb] *= alpha;
-#pragma unroll
-                    for (int b = 0; b < DVB; ++b)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[qb][b][i] *= alpha;
-                }
-                m_run[qb] = m_new;
-                float psum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int g = 0; g < 2; ++g) {
-                        float p[8];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][8 * g + j], scale_log2, -m_new));
-                            psum += p[j];
-                        }
-                        bf16x8 pk;
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) pk[j] = (__bf16)p[j];
-                        pb[qb][kb * 2 + g] = pk;
-                    }
-                l_run[qb] += psum;
-            }
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-                for (int b = 0; b < DVB; ++b) {
-                    const int r16 = lane & 15;
-                    const int dv = b * 32 + ((lane >> 4) & 1) * 16 + 4 * (r16 & 3);
-                    const int key0 = ks * 16 + 4 * half + (r16 >> 2);
-                    const s16x4 lo = lds_read_tr16(bV + key0 * ROWV + dv);
-                    const s16x4 hi = lds_read_tr16(bV + (key0 + 8) * ROWV + dv);
-                    bf16x8 a;
-                    __builtin_memcpy(&a, &lo, 8);
-                    __builtin_memcpy(reinterpret_cast<char *>(&a) + 8, &hi, 8);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-                        oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][ks], oacc[qb][b], 0, 0, 0);
-                }
-            }
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 w = lds_read_b128((lds + koff[s]) + KB);
+            __builtin_memcpy(&ka[s], &w, 16);
         }
-        if (kt + 1 < ntile) { ATT_STAGE_ALL(buf ^ 1) }
-        __syncthreads();
-    }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s0[i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], s0, 0, 0, 0);
+        ATT_FENCE
+        // operands of block 1 are fetched while the maximum of block 0 is worked out
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const u32x4 w = lds_read_b128((lds + koff[s]) + (KB + 32 * RB));
+            __builtin_memcpy(&ka[s], &w, 16);
+        }
+        if (RAGGED) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (8 * (i >> 2) + 4 * half + (i & 3) >= rem) s0[i] = -INFINITY;
+        }
+        ATT_NEW_MAX(s0, false)
+        // ---- scores of block 1 (matrix cores)  ||  probabilities of block 0 (vector ALU)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s1[i] = 0.f;
+        float psum = 0.f;
+        ATT_FENCE
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], s1, 0, 0, 0);
+            ATT_FENCE
+#pragma unroll
+            for (int e = EPC * s; e < EPC * s + EPC; e += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s0[e], scale_log2, -m_run));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s0[e + 1], scale_log2, -m_run));
+                pw[e >> 1] = pack_bf16x2(p0, p1);
+                psum = add_bf16x2(pw[e >> 1], psum);
+            }
+            ATT_FENCE
+        }
+        l_run += psum;
+        bf16x8 vop[2];                              // V^T operands, alternating so no copies are needed
+        vop[0] = load_v(0);
+        if (RAGGED) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (32 + 8 * (i >> 2) + 4 * half + (i & 3) >= rem) s1[i] = -INFINITY;
+        }
+        ATT_NEW_MAX(s1, true)
+        // ---- O^T += V^T P^T for block 0 (matrix cores)  ||  probabilities of block 1 (vector ALU)
+        psum = 0.f;
+        ATT_FENCE
+#pragma unroll
+        for (int idx = 0; idx < NPV; ++idx) {
+            vop[(idx + 1) & 1] = load_v(idx + 1);   // idx + 1 = NPV is the first operand of block 1
+            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[idx & 1], pb_operand(pw, idx / DVB),
+                                                                      oacc[idx % DVB], 0, 0, 0);
+            ATT_FENCE
+#pragma unroll
+            for (int e = EPV * idx; e < EPV * idx + EPV; e += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s1[e], scale_log2, -m_run));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s1[e + 1], scale_log2, -m_run));
+                pw[8 + (e >> 1)] = pack_bf16x2(p0, p1);
+                psum = add_bf16x2(pw[8 + (e >> 1)], psum);
+            }
+            ATT_FENCE
+        }
+        l_run += psum;
+        // ---- O^T += V^T P^T for block 1
+#pragma unroll
+        for (int idx = NPV; idx < 2 * NPV; ++idx) {
+            if (idx + 1 < 2 * NPV) vop[(idx + 1) & 1] = load_v(idx + 1);
+            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[idx & 1], pb_operand(pw, idx / DVB),
+                                                                      oacc[idx % DVB], 0, 0, 0);
+        }
+    };
+#undef ATT_FENCE
 
+
+    // Main loop, unrolled by two so that the LDS buffer index is a compile-time constant
+    // (every LDS address is then a per-lane base plus an immediate).  While tile kt is
+    // computed from buffer kt % 2, tile kt + 1 streams into the other buffer.
+#define ATT_STEP(BUFC)                                                                     \
+    {                                                                                      \
+        ATT_FETCH_ALL(kt + 1, 1 - BUFC)                                                    \
+        if (kt + 2 < ntile) { ATT_ROWS(kt + 2) }                                           \
+        if (wave_active) compute_tile(std::false_type{}, std::integral_constant<int, BUFC>{}, ATT_BN); \
+        __builtin_amdgcn_s_waitcnt(0x0F70);     /* vmcnt(0): the next tile is in LDS */    \
+        __syncthreads();                                                                   \
+        ++kt;                                                                              \
+    }
+    int kt = 0;
+    while (kt < ntile - 1) {                    // every tile but the last: full, and a next one to fetch
+        ATT_STEP(0)
+        if (kt >= ntile - 1) break;
+        ATT_STEP(1)
+    }
+    // the last tile (kept out of the loop so the loop body has a single path): maybe ragged
+    if (ntile > 0 && wave_active) {
+        const int rem = L - kt * ATT_BN;
+        if (kt & 1) {
+            if (rem < ATT_BN) compute_tile(std::true_type{}, std::integral_constant<int, 1>{}, rem);
+            else compute_tile(std::false_type{}, std::integral_constant<int, 1>{}, ATT_BN);
+        } else {
+            if (rem < ATT_BN) compute_tile(std::true_type{}, std::integral_constant<int, 0>{}, rem);
+            else compute_tile(std::false_type{}, std::integral_constant<int, 0>{}, ATT_BN);
+        }
+    }
+#undef ATT_STEP
+
+#undef ATT_NEW_MAX
 #undef ATT_ROWS
 #undef ATT_FETCH
-#undef ATT_STAGE
 #undef ATT_FETCH_ALL
-#undef ATT_STAGE_ALL
 
     // ---- epilogue: normalise, store at the original row
+    {
+        const int rl = wave * 32 + col;
+        if (rl < nrows) {
+            const int r = row0 + rl;
+            const size_t dst = (size_t)h * N + (perm_q ? perm_q[(size_t)h * N + r] : r);
+            const float l_tot = l_run + __shfl_xor(l_run, 32);
+            const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int rl = (wave * QB + qb) * 32 + col;
-        if (rl >= nrows) continue;
-        const int r = row0 + rl;
-        const size_t dst = (size_t)h * N + (perm_q ? perm_q[(size_t)h * N + r] : r);
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
+            for (int b = 0; b < DVB; ++b)
 #pragma unroll
-        for (int b = 0; b < DVB; ++b)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int dv0 = b * 32 + 8 * g + 4 * half;
-                unsigned lo = (unsigned)f32_to_bf16(oacc[qb][b][4 * g + 0] * inv) |
-                              ((unsigned)f32_to_bf16(oacc[qb][b][4 * g + 1] * inv) << 16);
-                unsigned hi = (unsigned)f32_to_bf16(oacc[qb][b][4 * g + 2] * inv) |
-                              ((unsigned)f32_to_bf16(oacc[qb][b][4 * g + 3] * inv) << 16);
-                *reinterpret_cast<uint2 *>(O + dst * D + dv0) = make_uint2(lo, hi);
-            }
-        if (lse && half == 0)
-            lse[dst] = (l_tot > 0.f) ? (m_run[qb] + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+                for (int g = 0; g < 4; ++g) {
+                    const int dv0 = b * 32 + 8 * g + 4 * half;
+                    unsigned lo = (unsigned)f32_to_bf16(oacc[b][4 * g + 0] * inv) |
+                                  ((unsigned)f32_to_bf16(oacc[b][4 * g + 1] * inv) << 16);
+                    unsigned hi = (unsigned)f32_to_bf16(oacc[b][4 * g + 2] * inv) |
+                                  ((unsigned)f32_to_bf16(oacc[b][4 * g + 3] * inv) << 16);
+                    *reinterpret_cast<uint2 *>(O + dst * D + dv0) = make_uint2(lo, hi);
+                }
+            if (lse && half == 0)
+                lse[dst] = (l_tot > 0.f) ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+        }
     }
 }
 
@@ -506,9 +617,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
 }
 
 // ---------------------------------------------------------------- host side
-static constexpr int ATT_QB = 1;                 // 32-query blocks per wavefront (bf16 kernel)
-
-static int attn_bm(int dtype) { return dtype == SVG2_BF16 ? 128 * ATT_QB : 64; }
+static int attn_bm(int dtype) { return dtype == SVG2_BF16 ? 128 : 64; }   // rows per tile
 
 size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
 {
@@ -574,16 +683,16 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
-        const size_t lds = (size_t)2 * ATT_BN * (2 * d + 40) * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
+        const size_t lds = (size_t)4 * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
                            (size_t)(Ck + 1) * sizeof(int2);
         if (d == 128) {
-            auto kern = attn_bf16_kernel<128, ATT_QB>;
+            auto kern = attn_bf16_kernel<128>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
                                tile_base, max_tiles, runs, row_keys, scale_log2, o, lse);
         } else {
-            auto kern = attn_bf16_kernel<64, ATT_QB>;
+            auto kern = attn_bf16_kernel<64>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
