@@ -176,6 +176,20 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
     return w;
 }
 
+// max / sum of a value with the one held by lane ^ 32 (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float max_xor32(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor32(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // acc + both bf16 halves of w (v_dot2c_f32_bf16 with a vector of ones): the row sum is taken
 // over the rounded probabilities, the same values the matrix cores multiply with V
 __device__ __forceinline__ float add_bf16x2(unsigned w, float acc)
@@ -309,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     {                                                                                      \
         float mx = fmaxf(fmaxf(S[0], S[1]), S[2]);                                         \
         _Pragma("unroll") for (int i = 3; i < 16; ++i) mx = fmaxf(mx, S[i]);               \
-        mx = fmaxf(mx, __shfl_xor(mx, 32));                                                \
+        mx = max_xor32(mx);                                                                \
         const float mx_s = mx * scale_log2;                                                \
         const bool upd = mx_s > m_run + 8.0f;                                              \
         if (__any(upd)) {                                                                  \
@@ -506,7 +520,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
         if (rl < nrows) {
             const int r = row0 + rl;
             const size_t dst = (size_t)h * N + (perm_q ? perm_q[(size_t)h * N + r] : r);
-            const float l_tot = l_run + __shfl_xor(l_run, 32);
+            const float l_tot = sum_xor32(l_run);
             const float inv = (l_tot > 0.f) ? 1.0f / l_tot : 0.f;
 #pragma unroll
             for (int b = 0; b < DVB; ++b)

@@ -25,3 +25,29 @@ def head_inputs(w: wl.Workload, heads):
     cq = np.stack([wl.init_centroids(w, h, Q[i], w.Cq, 0) for i, h in enumerate(heads)])
     ck = np.stack([wl.init_centroids(w, h, K[i], w.Ck, 1) for i, h in enumerate(heads)])
     return Q, K, V, cq, ck
+
+
+def assert_label_disagreements_are_near_ties(svg2, oracle, X, X_dev, init, iters, bf16, gpu_labels, ref_labels):
+    """The GPU's last assign step, judged on its own input: the centroids after iters - 1 GPU
+    iterations (k-means on the GPU is reproducible bit for bit, so re-running it gives the state the
+    last assign saw) go through ONE oracle assign step; wherever that disagrees with the GPU's labels
+    the token must be a near-tie (relative gap of its two smallest squared distances < 1e-3).
+    Against the oracle's own full run only the agreement rate is meaningful after several
+    iterations: an early near-tie flip moves centroids a little and later labels follow.
+    X [N,d] numpy, X_dev [1,N,d] device tensor of the same head, init [C,d] numpy."""
+    if np.array_equal(gpu_labels, ref_labels):
+        return 0
+    if iters > 1:
+        prev = svg2.svg2_kmeans(X_dev, torch.from_numpy(np.ascontiguousarray(init[None], dtype=np.float32)).cuda(),
+                                iters - 1).centroids
+        torch.cuda.synchronize()
+        prev = prev[0].cpu().numpy()
+    else:
+        prev = np.asarray(init, dtype=np.float32)
+    one = oracle.kmeans(X, prev, 1, bf16).labels
+    bad = np.nonzero(gpu_labels != one)[0]
+    if bad.size:
+        gap = oracle.top2_gap(X[bad], prev, bf16)
+        assert np.all(gap < 1e-3), "label disagreement away from a tie: gaps %s" % np.sort(gap)[-5:]
+    assert bad.size <= 1e-3 * gpu_labels.size
+    return int(bad.size)

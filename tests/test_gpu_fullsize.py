@@ -1,0 +1,165 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The whole Wan-like layer (H = 40, N = 75,600, d = 128, bf16) runs through
+svg2_forward once; three heads (first, middle, last) are then checked against
+the CPU oracle: labels, the permutation and CSR lists exactly (given the GPU's
+labels / centroids), and the attention output on a seeded sample of query rows
+(rows are independent, so the oracle computes exactly those rows).  A second
+case does the same for two heads of the Hunyuan-like shape (N = 118,800) and a
+third steps through a warm-started denoising sequence.
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_18875_amd import workloads as wl
+from _util import assert_label_disagreements_are_near_ties, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def svg2():
+    import paper_2505_18875_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def _csr_rows(row_ptr, col_idx):
+    return [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in range(len(row_ptr) - 1)]
+
+
+def _upload(w, heads):
+    """All requested heads as bf16 device tensors; host copies are kept only for `keep`."""
+    H = len(heads)
+    Q = torch.empty((H, w.N, w.d), dtype=torch.bfloat16, device="cuda")
+    K, V = torch.empty_like(Q), torch.empty_like(Q)
+    cq = torch.empty((H, w.Cq, w.d), dtype=torch.float32, device="cuda")
+    ck = torch.empty((H, w.Ck, w.d), dtype=torch.float32, device="cuda")
+
+    def gen(i):
+        h = heads[i]
+        q, k, v = wl.make_head(w, h)
+        return i, q, k, v, wl.init_centroids(w, h, q, w.Cq, 0), wl.init_centroids(w, h, k, w.Ck, 1)
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for i, q, k, v, a, b in ex.map(gen, range(H)):
+            Q[i], K[i], V[i] = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+            cq[i], ck[i] = to_dev(a), to_dev(b)
+    return Q, K, V, cq, ck
+
+
+def _check_heads(svg2, oracle, w, heads, check, Q, K, V, cq0, res, cq_out, ck_out, iters, n_rows, warm=None,
+                 compounded_min=0.999):
+    a = res.aux
+    for h in check:
+        i = heads.index(h)
+        q, k, v = to_np(Q[i]), to_np(K[i]), to_np(V[i])
+        init_q = to_np(cq0[0][i]) if warm is None else warm[0][i]
+        init_k = to_np(cq0[1][i]) if warm is None else warm[1][i]
+        kq = oracle.kmeans(q, init_q, iters, True)
+        kk = oracle.kmeans(k, init_k, iters, True)
+        lq, lk = to_np(a.labels_q[i]), to_np(a.labels_k[i])
+        for got, ref, X, Xd, init in ((lq, kq, q, Q[i:i + 1], init_q), (lk, kk, k, K[i:i + 1], init_k)):
+            # the oracle's own run from the same start (flips at near-ties compound over iterations) ...
+            agree = np.mean(got == ref.labels)
+            assert agree >= compounded_min, (h, agree)
+            # ... and the strict bar on the last assign step, judged on the GPU's own centroids
+            assert_label_disagreements_are_near_ties(svg2, oracle, X, Xd, init, iters, True, got, ref.labels)
+        pq, pk = oracle.permute(lq, w.Cq), oracle.permute(lk, w.Ck)
+        np.testing.assert_array_equal(to_np(a.perm_q[i]), pq.perm)
+        np.testing.assert_array_equal(to_np(a.perm_k[i]), pk.perm)
+        np.testing.assert_array_equal(to_np(a.offsets_q[i]), pq.offsets)
+        np.testing.assert_array_equal(to_np(a.offsets_k[i]), pk.offsets)
+        sel = oracle.select_topp(to_np(cq_out[i]), to_np(ck_out[i]), pq.counts, pk.counts, w.top_p)
+        rp, ci = to_np(a.row_ptr[i]), to_np(a.col_idx[i])
+        low = 0
+        for r_, (g, e) in enumerate(zip(_csr_rows(rp, ci), _csr_rows(sel.row_ptr, sel.col_idx))):
+            if sel.margin[r_] > 1e-5:
+                np.testing.assert_array_equal(g, e)
+            else:
+                low += 1
+        assert low <= max(2, w.Cq // 20)
+        rows = np.sort(np.random.default_rng(h).choice(w.N, n_rows, replace=False)).astype(np.int32)
+        O_ref, lse_ref = oracle.sparse_attention(q[pq.perm], k[pk.perm], v[pk.perm], pq.offsets, pk.offsets, rp,
+                                                 ci[: rp[-1]], perm_q=pq.perm, rows=rows)
+        chk = pq.perm[rows]
+        err = np.abs(to_np(res.O[i])[chk] - O_ref[chk])
+        assert err.max() <= 2e-2 and err.mean() <= 1e-3, (h, err.max(), err.mean())
+        np.testing.assert_allclose(to_np(a.lse[i])[chk], lse_ref[chk], rtol=1e-3, atol=2e-3)
+        keys = np.array([pk.counts[c].sum() for c in _csr_rows(rp, ci)])
+        np.testing.assert_allclose(float(a.density[i]), (pq.counts * keys).sum() / float(w.N) ** 2, rtol=1e-5)
+
+
+def test_wan_like_layer_full_size(svg2, oracle):
+    w = wl.WORKLOADS["wan_like"]
+    heads = list(range(w.H))
+    Q, K, V, cq, ck = _upload(w, heads)
+    cq0, ck0 = cq.clone(), ck.clone()
+    res = svg2.svg2_forward(Q, K, V, cq, ck, w.top_p, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    dens = res.aux.density.cpu().numpy()
+    assert np.all((dens > 0.05) & (dens < 0.6))          # the operating range the workload was calibrated for
+    _check_heads(svg2, oracle, w, heads, [0, 19, 39], Q, K, V, (cq0, ck0), res, cq, ck, w.iters, 256)
+    # properties that hold for every head at any size
+    a = res.aux
+    assert torch.equal(a.offsets_q[:, -1], torch.full((w.H,), w.N, dtype=torch.int32, device="cuda"))
+    assert torch.equal(torch.sort(a.perm_k, dim=1).values,
+                       torch.arange(w.N, dtype=torch.int32, device="cuda").expand(w.H, -1))
+    assert torch.equal(a.counts_k.sum(dim=1), torch.full((w.H,), w.N, device="cuda"))
+    assert bool(torch.isfinite(res.O.float()).all())
+
+
+def test_hunyuan_like_two_heads_full_length(svg2, oracle):
+    w = wl.WORKLOADS["hunyuan_like"]
+    heads = [0, 23]
+    Q, K, V, cq, ck = _upload(w, heads)
+    cq0, ck0 = cq.clone(), ck.clone()
+    res = svg2.svg2_forward(Q, K, V, cq, ck, w.top_p, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    # On the rank^-1.1 cluster sizes the big components are split between several centroids whose
+    # borders are soft, so one near-tie flip in an early iteration grows into ~1 % different labels
+    # ten iterations later; the per-step bar (99.9 %, near-ties only) is enforced for every iteration
+    # below and inside _check_heads for the last one.
+    _check_heads(svg2, oracle, w, heads, heads, Q, K, V, (cq0, ck0), res, cq, ck, w.iters, 192, compounded_min=0.98)
+    from _util import assert_label_disagreements_are_near_ties as near_ties
+    Kh, init = to_np(K[0]), to_np(ck0[0])
+    for t in range(1, w.iters + 1):
+        g = svg2.svg2_kmeans(K[0:1], ck0[0:1].clone(), t)
+        torch.cuda.synchronize()
+        flips = near_ties(svg2, oracle, Kh, K[0:1], init, t, True, to_np(g.labels[0]), np.full(w.N, -1, np.int32))
+        assert flips <= 1e-3 * w.N, (t, flips)
+
+
+def test_top_p_one_equals_dense_on_zipf_clusters(svg2, oracle):
+    # Section 4.1 equivalence on the skewed (rank^-1.1) cluster sizes of the Hunyuan-like recipe, reduced length
+    w = wl.replace(wl.WORKLOADS["hunyuan_like"], grid=(3, 20, 40), top_p=1.0, iters=3)
+    Q, K, V, cq, ck = _upload(w, [0])
+    res = svg2.svg2_forward(Q, K, V, cq, ck, 1.0, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    rows = np.sort(np.random.default_rng(0).choice(w.N, 256, replace=False))
+    O_ref, _ = oracle.dense_attention(to_np(Q[0])[rows], to_np(K[0]), to_np(V[0]))
+    err = np.abs(to_np(res.O[0])[rows] - O_ref)
+    assert err.max() <= 2e-2 and err.mean() <= 1e-3
+    assert float(res.aux.density[0]) == pytest.approx(1.0, rel=1e-6)
+
+
+def test_denoising_sequence_with_centroid_cache(svg2, oracle):
+    # Section 4.3: each step warm-starts k-means from the previous step's centroids (2 iterations).
+    w = wl.replace(wl.WORKLOADS["wan_like"], grid=(6, 30, 40), iters=10)
+    heads = [0, 1]
+    Q, K, V, cq, ck = _upload(w, heads)
+    Qh, Kh = to_np(Q), to_np(K)
+    res = svg2.svg2_forward(Q, K, V, cq, ck, w.top_p, w.iters, want_aux=True)      # step 0: seeded start
+    torch.cuda.synchronize()
+    for step in range(1, 4):
+        Qh = np.stack([wl.drift(w, h, step, Qh[i], 0) for i, h in enumerate(heads)])
+        Kh = np.stack([wl.drift(w, h, step, Kh[i], 1) for i, h in enumerate(heads)])
+        Q, K = to_dev(Qh, "bf16"), to_dev(Kh, "bf16")
+        warm = (to_np(cq), to_np(ck))                                              # the cache as the GPU left it
+        cq_before = (cq.clone(), ck.clone())
+        res = svg2.svg2_forward(Q, K, V, cq, ck, w.top_p, 2, want_aux=True)
+        torch.cuda.synchronize()
+        _check_heads(svg2, oracle, w, heads, heads, Q, K, V, cq_before, res, cq, ck, 2, 192, warm=warm)
