@@ -30,9 +30,10 @@ sys.path.insert(0, ROOT)
 from paper_2505_18875_amd import workloads as wl  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak
-# HBM bytes per attention-kernel launch from rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.
-ATTN_TRAFFIC_BYTES = None
+# HBM-side bytes per attention-kernel launch on the Wan-like layer at top-p 0.9, from two
+# rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy in the
+# same runs): profiles/wan_like_attention_hbm_traffic.md.  Other workloads report null.
+ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 60948150.2 + 777799.1) * 1024.0}
 
 
 def _gen_head(args):
@@ -122,6 +123,8 @@ def main():
     ap.add_argument("--iters", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -149,6 +152,14 @@ def main():
     if not torch.cuda.is_available():
         raise RuntimeError("bench.py needs a GPU")
     Q, K, V, cq0, ck0 = upload_inputs(w, gen, log)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy calibration: one device copy of %d bytes" % src.numel())
+        del src, dst
 
     total = args.warmup + args.steps
     # every step starts from the same seeded centroids: one in/out buffer pair per step, filled beforehand
@@ -197,7 +208,7 @@ def main():
         "stages_ms": stage_ms,
         "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES, "flops_per_launch": sel_flops, "ms_per_launch": attn_ms},
+                     "traffic": ATTN_TRAFFIC_BYTES.get((w.name, w.top_p)) if w.iters == wl.WORKLOADS[w.name].iters else None, "flops_per_launch": sel_flops, "ms_per_launch": attn_ms},
     }
 
     if not args.no_dense:

@@ -22,6 +22,7 @@
 //
 // The result of sorted row r is stored at row perm_q[r] (Section 4.1: the
 // inverse query permutation restores the original order).
+#include <cstdlib>
 #include <type_traits>
 
 #include "svg2_common.h"
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base, int max_tiles,
-    const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2,
+    const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2, int group,
     bf16_t *__restrict__ O, float *__restrict__ lse)
 {
     constexpr int KS = D / 16;                 // k-steps of QK^T
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     // consecutive tiles per XCD, so tiles that share keys share an L2 and every XCD
     // gets the same amount of work whatever the per-head densities are.
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const int v = (slot / ATT_GROUP) * (8 * ATT_GROUP) + xcd * ATT_GROUP + slot % ATT_GROUP;
+    const int v = (slot / group) * (8 * group) + xcd * group + slot % group;
     if (v >= tile_base[H]) return;
     int h = 0;
     for (int step = 1 << 15; step > 0; step >>= 1)
@@ -692,7 +693,9 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)d);
     if (dtype == SVG2_BF16) {
         const int total = H * max_tiles;
-        const int nwg = cdiv(total, 8 * ATT_GROUP) * 8 * ATT_GROUP;
+        int group = ATT_GROUP;
+        if (const char *e = getenv("SVG2_ATT_GROUP")) group = atoi(e) > 0 ? atoi(e) : group;
+        const int nwg = cdiv(total, 8 * group) * 8 * group;
         const float scale_log2 = scale * 1.4426950408889634f;
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
@@ -704,13 +707,13 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               tile_base, max_tiles, runs, row_keys, scale_log2, o, lse);
+                               tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         } else {
             auto kern = attn_bf16_kernel<64>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               tile_base, max_tiles, runs, row_keys, scale_log2, o, lse);
+                               tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         }
     } else {
         const float *q = static_cast<const float *>(Qp), *k = static_cast<const float *>(Kp),
