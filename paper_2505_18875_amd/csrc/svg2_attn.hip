@@ -22,7 +22,6 @@
 //
 // The result of sorted row r is stored at row perm_q[r] (Section 4.1: the
 // inverse query permutation restores the original order).
-#include <cstdlib>
 #include <type_traits>
 
 #include "svg2_common.h"
@@ -693,8 +692,7 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)d);
     if (dtype == SVG2_BF16) {
         const int total = H * max_tiles;
-        int group = ATT_GROUP;
-        if (const char *e = getenv("SVG2_ATT_GROUP")) group = atoi(e) > 0 ? atoi(e) : group;
+        const int group = ATT_GROUP;
         const int nwg = cdiv(total, 8 * group) * 8 * group;
         const float scale_log2 = scale * 1.4426950408889634f;
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
