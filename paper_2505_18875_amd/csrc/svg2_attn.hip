@@ -34,7 +34,13 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 static constexpr int ATT_BN = 64;          // keys per tile
+// Launch shape of the bf16 kernel.  Measured on the Wan-like layer (8-head probe, ms sparse / dense):
+// 4 wavefronts, 2 buffers, 2 workgroups per CU 7.76 / 24.5;  8 wavefronts, 3 buffers, 1 workgroup per CU
+// (half the L2 -> LDS traffic, but 8 wavefronts behind one barrier) 8.17 / 25.7.
 static constexpr int ATT_GROUP = 8;        // consecutive tiles handed to one XCD
+static constexpr int ATT_NW = 4;           // wavefronts per workgroup of the bf16 kernel, 32 queries each
+static constexpr int ATT_NSTG = 2;         // K and V tile buffers in LDS (each): 2 or 3
+static constexpr int ATT_OPS_B = 0;        // vector operations of a block's probabilities done early (see phase B)
 
 // ---------------------------------------------------------------- plan
 // grid (H), block 256.
@@ -209,7 +215,7 @@ __device__ __forceinline__ bf16x8 pb_operand(const unsigned *pw, int k)
 }
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
+__global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base, int max_tiles,
@@ -221,18 +227,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     constexpr int RB = 2 * D;                  // bytes per K / V row
     constexpr int CPR = D / 8;                 // 16-byte chunks per row
     constexpr int RPI = 1024 / RB;             // rows one direct-to-LDS load instruction fills (64 lanes x 16 B)
-    constexpr int NPASS = ATT_BN / (4 * RPI);  // such instructions per wavefront, tile and tensor
+    constexpr int NW = ATT_NW, NSTG = ATT_NSTG;
+    constexpr int NPASS = ATT_BN / (NW * RPI); // such instructions per wavefront, tile and tensor
+    static_assert(NPASS >= 1, "a tile needs at least one load instruction per wavefront");
     constexpr int TILE_B = ATT_BN * RB;        // bytes of one K or V tile in LDS
 
-    // LDS: K tiles [2][64][D] and V tiles [2][64][D], rows unpadded (the direct loads
+    // LDS: K tiles [NSTG][64][D] and V tiles [NSTG][64][D], rows unpadded (the direct loads
     // fill 1024 contiguous bytes per instruction); bank conflicts are avoided by
     // storing 16-byte chunk c of row r at position c ^ swz(r):
     //   K  swz = (r / (256 / RB)) % CPR        the 16 rows of one ds_read_b128 pass differ
     //   V  swz = 4 * ((r / (256 / RB)) % (CPR / 4))   the 4 rows of one transposing pass differ
     extern __shared__ __align__(16) unsigned char s_raw[];
-    unsigned char *sK = s_raw;                                      // [2][TILE_B]
-    unsigned char *sV = s_raw + 2 * TILE_B;                         // [2][TILE_B]
-    int32_t *s_rows = reinterpret_cast<int32_t *>(s_raw + 4 * TILE_B);   // [2][64]
+    unsigned char *sK = s_raw;                                      // [NSTG][TILE_B]
+    unsigned char *sV = s_raw + NSTG * TILE_B;                      // [NSTG][TILE_B]
+    int32_t *s_rows = reinterpret_cast<int32_t *>(s_raw + 2 * NSTG * TILE_B);   // [2][64]
     int2 *s_run = reinterpret_cast<int2 *>(s_rows + 2 * ATT_BN);    // [nnz + 1]
 
     // ---- which work item.  All tiles of all heads form one list (head-major, so
@@ -258,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     const int nnz = row_ptr[(size_t)h * (Cq + 1) + ci + 1] - e0;
     const int L = row_keys[(size_t)h * Cq + ci];
     const int2 *rn = runs + (size_t)h * Cq * Ck + e0;
-    for (int e = tid; e < nnz; e += 256) s_run[e] = rn[e];
+    for (int e = tid; e < nnz; e += 64 * NW) s_run[e] = rn[e];
     if (tid == 0) s_run[nnz] = make_int2(0, L);
 
     const bf16_t *Qh = Q + (size_t)h * N * D;
@@ -286,11 +294,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
         for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
 
     // ---- loader.  The permuted K / V row of every key slot of a tile is looked up by
-    // ONE wavefront (wave kt % 4, lane = slot) two tiles ahead and parked in s_rows.
-    // The rows then go from global memory straight into LDS (no staging registers):
-    // load instruction (wave, p) fills LDS rows (4 p + wave) * RPI .. + RPI of the tile,
-    // lane l the chunk position l % CPR of row l / CPR, so it fetches the global chunk
-    // that the swizzle puts there.
+    // ONE wavefront (wave kt % NW, lane = slot) ahead of time and parked in s_rows.  The
+    // rows then go from global memory straight into LDS (no staging registers): load
+    // instruction (wave, p) fills LDS rows (NW p + wave) * RPI .. + RPI of the tile, lane l
+    // the chunk position l % CPR of row l / CPR, so it fetches the global chunk that the
+    // swizzle puts there.  K tiles are fetched three tiles ahead of their use and V tiles
+    // two tiles ahead (see the schedule below), so the byte offsets of a tile's rows are
+    // kept in registers from its K fetch to its V fetch.
     const char *Kb = reinterpret_cast<const char *>(Kh);
     const char *Vb = reinterpret_cast<const char *>(Vh);
     int cur = 0;
@@ -301,52 +311,44 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
     __syncthreads();                            // s_run visible
 
 #define ATT_ROWS(KT)                                                                       \
-    if (wave == ((KT) & 3)) {                                                              \
+    if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
         s_rows[((KT) & 1) * ATT_BN + lane] = (kk < L) ? run_lookup(s_run, cur, kk) : 0;    \
     }
-#define ATT_FETCH(P, KT, BUF)                                                              \
-    if (P < NPASS) {                                                                       \
-        const int grp_ = (4 * P + wave) * RPI;                                             \
-        const unsigned off_ = (unsigned)s_rows[((KT) & 1) * ATT_BN + grp_ + ld_row] * (unsigned)RB;        \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Kb + (off_ + ld_koff)), \
-                                         (__attribute__((address_space(3))) void *)(sK + (BUF) * TILE_B + grp_ * RB), 16, 0, 0); \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Vb + (off_ + ld_voff)), \
-                                         (__attribute__((address_space(3))) void *)(sV + (BUF) * TILE_B + grp_ * RB), 16, 0, 0); \
-    }
-// Online-softmax bookkeeping for one block of 32 scores per query (16 per lane, the
-// other 16 in lane ^ 32).  The running maximum only moves when it would grow by
-// more than 2^8, so probabilities stay below 256 and the rescaling of the output
-// accumulators is rare.  FIX_PB: block 0's probabilities (pw[0..7]) are already
-// computed but not yet accumulated, so they are rescaled too.
-#define ATT_NEW_MAX(S, FIX_PB)                                                             \
-    {                                                                                      \
-        float mx = fmaxf(fmaxf(S[0], S[1]), S[2]);                                         \
-        _Pragma("unroll") for (int i = 3; i < 16; ++i) mx = fmaxf(mx, S[i]);               \
-        mx = max_xor32(mx);                                                                \
-        const float mx_s = mx * scale_log2;                                                \
-        const bool upd = mx_s > m_run + 8.0f;                                              \
-        if (__any(upd)) {                                                                  \
-            const float m_new = upd ? mx_s : m_run;                                        \
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);                     \
-            m_run = m_new;                                                                 \
-            l_run *= alpha;                                                                \
-            _Pragma("unroll") for (int b = 0; b < DVB; ++b)                                \
-                _Pragma("unroll") for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;        \
-            if (FIX_PB) {                                                                  \
-                _Pragma("unroll") for (int j = 0; j < 8; ++j)                              \
-                    pw[j] = pack_bf16x2(__uint_as_float(pw[j] << 16) * alpha,              \
-                                        __uint_as_float(pw[j] & 0xFFFF0000u) * alpha);     \
-            }                                                                              \
-        }                                                                                  \
-    }
-#define ATT_FETCH_ALL(KT, BUF) ATT_FETCH(0, KT, BUF) ATT_FETCH(1, KT, BUF) ATT_FETCH(2, KT, BUF) ATT_FETCH(3, KT, BUF)
+#define ATT_OFFS(KT, OFF)                                                                  \
+    _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
+        OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row] * (unsigned)RB;
+#define ATT_FETCH(OFF, SRC, LOFF, DST)                                                     \
+    _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(SRC + (OFF[p_] + LOFF)), \
+                                         (__attribute__((address_space(3))) void *)(DST + ((NW * p_ + wave) * RPI) * RB), 16, 0, 0);
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
+    unsigned off_nx[NPASS];                     // row offsets of the tile whose V is fetched next
     ATT_ROWS(0)
     ATT_ROWS(1)
     __syncthreads();
-    if (ntile > 0) { ATT_FETCH_ALL(0, 0) }
+    if (ntile > 0) {
+        ATT_OFFS(0, off_nx)
+        ATT_FETCH(off_nx, Kb, ld_koff, sK)
+        ATT_FETCH(off_nx, Vb, ld_voff, sV)
+    }
+    if (ntile > 1) {
+        ATT_OFFS(1, off_nx)
+        ATT_FETCH(off_nx, Kb, ld_koff, sK + TILE_B)
+        if (NSTG > 2) { ATT_FETCH(off_nx, Vb, ld_voff, sV + TILE_B) }
+    }
+    __syncthreads();                            // everyone has read the rows of tiles 0 and 1
+    if (ntile > 2) { ATT_ROWS(2) }
+    if (NSTG > 2) {
+        if (ntile > 3) { ATT_ROWS(3) }
+        __syncthreads();
+        if (ntile > 2) {
+            ATT_OFFS(2, off_nx)
+            ATT_FETCH(off_nx, Kb, ld_koff, sK + 2 * TILE_B)
+        }
+    }
+    // off_nx stays live: it holds the rows of tile NSTG - 1, whose V is requested at the top of tile 0
     // per-lane LDS read offsets (bytes, buffer 0): K operand of k-step s, V^T operand of column block b
     int koff[KS], voff[DVB];
     {
@@ -360,159 +362,229 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(
 #pragma unroll
         for (int b = 0; b < DVB; ++b) voff[b] = kr0 * RB + ((((4 * b) ^ vz) + cl) * 16) + (r16 & 1) * 8;
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): queries and the first tile have landed
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): queries and the first tiles have landed
     __syncthreads();
 
-    // One 64-key tile of this wavefront's 32 queries, from LDS buffer `buf`.  RAGGED: keys
-    // past `rem` do not exist (end of the key sequence) and get a score of -inf.
+    // ---- schedule.  The key sequence is consumed in blocks of 32 keys (two per 64-key
+    // tile).  Per block j the work is S_j = K_j Q^T (KS matrix instructions), the running
+    // maximum, P_j = exp2(S_j - m) (vector ALU, 6 operations per pair of scores: two fma,
+    // two exp2, one pack to bf16, one row-sum dot) and O^T += V_j^T P_j^T (NPV matrix
+    // instructions).  The blocks are software-pipelined so that every matrix instruction
+    // has about the same amount of independent vector work in its shadow:
     //
-    // The tile is two blocks of 32 keys, each with its own online-softmax step, and the
-    // instruction stream is laid out by hand (ATT_FENCE keeps the compiler from moving
-    // code across chunk boundaries): every matrix instruction of the second score block
-    // is followed by the vector work (exp2, row sum, bf16 packing) of 16 / KS scores of
-    // the first block, and every matrix instruction that accumulates the first block
-    // into the output by the vector work of the second block.  One matrix instruction
-    // keeps the cores busy for 32 cycles, about what 7 vector instructions take.
-    // Accumulator i of a block is key 8 (i/4) + 4 half + i%4 of that block.
+    //   phase A(j):  S_{j+1} = K_{j+1} Q^T   ||  last two thirds of P_j, LDS reads of V_j^T
+    //   phase B(j):  O^T += V_j^T P_j^T      ||  maximum of S_{j+1} and the decision about the
+    //                                            running maximum (first half), first third of
+    //                                            P_{j+1} (second half), LDS reads of K_{j+2}
+    //
+    // The instruction stream is laid out by hand (ATT_FENCE keeps the compiler from moving
+    // code across chunk boundaries).  The running maximum only moves when it would grow by
+    // more than 2^8 (probabilities stay below 256), so rescaling the output accumulators is
+    // rare; it is applied at the end of phase B, when block j has been accumulated under the
+    // old maximum.  Accumulator i of a block is key 8 (i/4) + 4 half + i%4.
+    //
+    // Tile t lives in K buffer t % 2 and V buffer t % 2.  One barrier per tile: at the top of
+    // tile t every wavefront has finished tile t - 1 and all fetches issued a tile ago have
+    // landed; then V_{t+1} and K_{t+2} are requested (K is read one and a half blocks ahead
+    // of V, so it is fetched a tile earlier).
 #define ATT_FENCE __builtin_amdgcn_sched_barrier(0);
-    auto compute_tile = [&](auto ragged_tag, auto buf_tag, int rem) {
-        constexpr bool RAGGED = decltype(ragged_tag)::value;
-        constexpr int BUF = decltype(buf_tag)::value;
-        constexpr int EPC = 16 / KS;               // scores handled per chunk of score-block work
-        constexpr int NPV = 2 * DVB;               // matrix instructions per block in O^T += V^T P^T
-        constexpr int EPV = 16 / NPV;              // scores handled per chunk there
-        // LDS addresses are a per-lane 32-bit base plus a compile-time constant, which the
-        // DS instructions take as their immediate offset
-        const lds_u8 *lds = (const lds_u8 *)s_raw;
-        constexpr int KB = BUF * TILE_B, VB = 2 * TILE_B + BUF * TILE_B;
-        // V^T operand of matrix instruction idx (ks = idx / DVB: 16 keys, b = idx % DVB: 32 output columns)
-        auto load_v = [&](int idx) {
-            const int ks = idx / DVB, b = idx % DVB;
-            const s16x4 lo = lds_read_tr16((lds + voff[b]) + (VB + (ks * 16) * RB));
-            const s16x4 hi = lds_read_tr16((lds + voff[b]) + (VB + (ks * 16 + 8) * RB));
-            bf16x8 a;
-            __builtin_memcpy(&a, &lo, 8);
-            __builtin_memcpy(reinterpret_cast<char *>(&a) + 8, &hi, 8);
-            return a;
-        };
-        f32x16 s0, s1;
-        unsigned pw[16];                            // probabilities, two bf16 per word; 4 words = one B operand
-        bf16x8 ka[KS];
-        // ---- scores of block 0
+// An empty volatile asm that "modifies" a value: the value has to exist at this point of the
+// program, so optimisation passes that work above the instruction scheduler cannot sink the
+// vector work out of the chunk it was written in.
+#define ATT_PIN(X) asm volatile("" : "+v"(X));
+    constexpr int NPV = 2 * DVB;
+    constexpr int NOPS = 48;                    // vector operations of one block's probabilities
+    constexpr int OPS_B = ATT_OPS_B;            // of which phase B (of the block before) does the first OPS_B
+    const lds_u8 *lds = (const lds_u8 *)s_raw;
+    f32x16 s0, s1;                              // scores of block 0 / block 1 of a tile
+    unsigned pw0[8], pw1[8];                    // probabilities of block 0 / block 1, two bf16 per word
+    bf16x8 ka[KS], va[NPV];                     // K operands of the next score block, V^T operands of this one
+    float psum = 0.f, alpha = 1.f, t0 = 0.f, t1 = 0.f;
+    bool any_upd = false;
+
+    // operation `op` (0..47) of the probabilities of one block: S -> pw
+    auto exp_op = [&](const f32x16 &S, unsigned *pw, int op) {
+        const int e = op / 6, k = op % 6;
+        if (k == 0) { t0 = fmaf(S[2 * e], scale_log2, -m_run); ATT_PIN(t0) }
+        else if (k == 1) { t1 = fmaf(S[2 * e + 1], scale_log2, -m_run); ATT_PIN(t1) }
+        else if (k == 2) { t0 = __builtin_amdgcn_exp2f(t0); ATT_PIN(t0) }
+        else if (k == 3) { t1 = __builtin_amdgcn_exp2f(t1); ATT_PIN(t1) }
+        else if (k == 4) { pw[e] = pack_bf16x2(t0, t1); ATT_PIN(pw[e]) }
+        else { psum = add_bf16x2(pw[e], psum); ATT_PIN(psum) }
+    };
+    auto mask_block = [&](f32x16 &S, int base, int rem) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (base + 8 * (i >> 2) + 4 * half + (i & 3) >= rem) S[i] = -INFINITY;
+    };
+    // the decision about the running maximum, given the maximum mx of a new score block
+    auto decide = [&](float mx) {
+        const float mx_s = max_xor32(mx) * scale_log2;
+        const bool upd = mx_s > m_run + 8.0f;
+        any_upd = __any(upd);
+        const float m_new = upd ? mx_s : m_run;
+        alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        ATT_PIN(m_run)
+        ATT_PIN(alpha)
+        psum = 0.f;
+    };
+    // K operands of a score block: KBYTE = byte offset of the block's first row in LDS
+    auto load_k = [&](auto kbyte_tag, int s) {
+        constexpr int KBYTE = decltype(kbyte_tag)::value;
+        const u32x4 w = lds_read_b128((lds + koff[s]) + KBYTE);
+        __builtin_memcpy(&ka[s], &w, 16);
+    };
+    // V^T operand idx of a block (ks = idx / DVB: 16 keys, b = idx % DVB: 32 output columns)
+    auto load_v = [&](auto vbyte_tag, int idx) {
+        constexpr int VBYTE = decltype(vbyte_tag)::value;
+        const int ks = idx / DVB, b = idx % DVB;
+        const s16x4 lo = lds_read_tr16((lds + voff[b]) + (VBYTE + (ks * 16) * RB));
+        const s16x4 hi = lds_read_tr16((lds + voff[b]) + (VBYTE + (ks * 16 + 8) * RB));
+        __builtin_memcpy(&va[idx], &lo, 8);
+        __builtin_memcpy(reinterpret_cast<char *>(&va[idx]) + 8, &hi, 8);
+    };
+    // phase A: Sacc = K Q^T from ka[] (if DO_S)  ||  operations 16..47 of pw = exp2(Sexp - m), V^T operands from VBYTE
+    auto phase_a = [&](auto do_s_tag, auto vbyte_tag, f32x16 &Sacc, const f32x16 &Sexp, unsigned *pw) {
+        constexpr bool DO_S = decltype(do_s_tag)::value;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const u32x4 w = lds_read_b128((lds + koff[s]) + KB);
-            __builtin_memcpy(&ka[s], &w, 16);
+            if (DO_S) {
+                if (s == 0) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) Sacc[i] = 0.f;
+                }
+                Sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], Sacc, 0, 0, 0);
+            }
+            ATT_FENCE
+#pragma unroll
+            for (int idx = (2 * NPV * s) / KS; idx < (2 * NPV * (s + 1)) / KS && idx < NPV; ++idx)
+                load_v(vbyte_tag, idx);         // all issued in the first half, so they have landed by phase B
+#pragma unroll
+            for (int op = OPS_B + ((NOPS - OPS_B) * s) / KS; op < OPS_B + ((NOPS - OPS_B) * (s + 1)) / KS; ++op)
+                exp_op(Sexp, pw, op);
+            ATT_FENCE
         }
+        l_run += psum;
+    };
+    // phase B: O^T += V^T P^T from va[] and pr[]  ||  maximum of Snext and the decision, then operations
+    // 0..15 of pn = exp2(Snext - m) (if DO_MAX); K operands of the block after Snext from KBYTE (if DO_K)
+    auto phase_b = [&](auto do_max_tag, auto do_k_tag, auto kbyte_tag, const unsigned *pr, const f32x16 &Snext,
+                       unsigned *pn) {
+        constexpr bool DO_MAX = decltype(do_max_tag)::value;
+        constexpr bool DO_K = decltype(do_k_tag)::value;
+        constexpr int HB = NPV / 2;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int idx = 0; idx < NPV; ++idx) {
+            bf16x8 pb;
+            __builtin_memcpy(&pb, pr + 4 * (idx / DVB), 16);
+            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[idx], pb, oacc[idx % DVB], 0, 0, 0);
+            ATT_FENCE
+            if (DO_K) {
+#pragma unroll
+                for (int s = (KS * idx) / NPV; s < (KS * (idx + 1)) / NPV; ++s) load_k(kbyte_tag, s);
+            }
+            if (DO_MAX && idx < HB) {
+#pragma unroll
+                for (int c = (8 * idx) / HB; c < (8 * (idx + 1)) / HB; ++c) {
+                    if (c == 0) mx = fmaxf(fmaxf(Snext[0], Snext[1]), Snext[2]);
+                    else if (c < 7) mx = fmaxf(fmaxf(mx, Snext[2 * c + 1]), Snext[2 * c + 2]);
+                    else mx = fmaxf(mx, Snext[15]);
+                    ATT_PIN(mx)
+                }
+                if (idx == HB - 1) decide(mx);
+            }
+            if (DO_MAX && idx >= HB) {
+#pragma unroll
+                for (int op = (OPS_B * (idx - HB)) / HB; op < (OPS_B * (idx - HB + 1)) / HB; ++op)
+                    exp_op(Snext, pn, op);
+            }
+            ATT_FENCE
+        }
+        if (DO_MAX && any_upd) {
+            l_run *= alpha;
+#pragma unroll
+            for (int b = 0; b < DVB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
+        }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+
+    // ---- prologue: S of block 0 of tile 0, its maximum, the first third of its probabilities,
+    // K operands of block 1
+    if (wave_active && ntile > 0) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) load_k(std::integral_constant<int, 0>{}, s);
 #pragma unroll
         for (int i = 0; i < 16; ++i) s0[i] = 0.f;
 #pragma unroll
         for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], s0, 0, 0, 0);
-        ATT_FENCE
-        // operands of block 1 are fetched while the maximum of block 0 is worked out
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const u32x4 w = lds_read_b128((lds + koff[s]) + (KB + 32 * RB));
-            __builtin_memcpy(&ka[s], &w, 16);
-        }
-        if (RAGGED) {
+        for (int s = 0; s < KS; ++s) load_k(std::integral_constant<int, 32 * RB>{}, s);
+        if (L < 32) mask_block(s0, 0, L);
+        float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (8 * (i >> 2) + 4 * half + (i & 3) >= rem) s0[i] = -INFINITY;
-        }
-        ATT_NEW_MAX(s0, false)
-        // ---- scores of block 1 (matrix cores)  ||  probabilities of block 0 (vector ALU)
+        for (int i = 3; i < 16; ++i) mx = fmaxf(mx, s0[i]);
+        decide(mx);                             // key 0 exists, so the maximum is finite; nothing to rescale yet
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s1[i] = 0.f;
-        float psum = 0.f;
-        ATT_FENCE
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], s1, 0, 0, 0);
-            ATT_FENCE
-#pragma unroll
-            for (int e = EPC * s; e < EPC * s + EPC; e += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s0[e], scale_log2, -m_run));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s0[e + 1], scale_log2, -m_run));
-                pw[e >> 1] = pack_bf16x2(p0, p1);
-                psum = add_bf16x2(pw[e >> 1], psum);
-            }
-            ATT_FENCE
-        }
-        l_run += psum;
-        bf16x8 vop[2];                              // V^T operands, alternating so no copies are needed
-        vop[0] = load_v(0);
-        if (RAGGED) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (32 + 8 * (i >> 2) + 4 * half + (i & 3) >= rem) s1[i] = -INFINITY;
-        }
-        ATT_NEW_MAX(s1, true)
-        // ---- O^T += V^T P^T for block 0 (matrix cores)  ||  probabilities of block 1 (vector ALU)
-        psum = 0.f;
-        ATT_FENCE
-#pragma unroll
-        for (int idx = 0; idx < NPV; ++idx) {
-            vop[(idx + 1) & 1] = load_v(idx + 1);   // idx + 1 = NPV is the first operand of block 1
-            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[idx & 1], pb_operand(pw, idx / DVB),
-                                                                      oacc[idx % DVB], 0, 0, 0);
-            ATT_FENCE
-#pragma unroll
-            for (int e = EPV * idx; e < EPV * idx + EPV; e += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s1[e], scale_log2, -m_run));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s1[e + 1], scale_log2, -m_run));
-                pw[8 + (e >> 1)] = pack_bf16x2(p0, p1);
-                psum = add_bf16x2(pw[8 + (e >> 1)], psum);
-            }
-            ATT_FENCE
-        }
-        l_run += psum;
-        // ---- O^T += V^T P^T for block 1
-#pragma unroll
-        for (int idx = NPV; idx < 2 * NPV; ++idx) {
-            if (idx + 1 < 2 * NPV) vop[(idx + 1) & 1] = load_v(idx + 1);
-            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop[idx & 1], pb_operand(pw, idx / DVB),
-                                                                      oacc[idx % DVB], 0, 0, 0);
-        }
-    };
-#undef ATT_FENCE
+        for (int op = 0; op < OPS_B; ++op) exp_op(s0, pw0, op);
+    }
 
-
-    // Main loop, unrolled by two so that the LDS buffer index is a compile-time constant
-    // (every LDS address is then a per-lane base plus an immediate).  While tile kt is
-    // computed from buffer kt % 2, tile kt + 1 streams into the other buffer.
-#define ATT_STEP(BUFC)                                                                     \
+    // One tile: tile kt sits in K / V buffer BUF = kt % NSTG.  HAS_NEXT: tile kt + 1 exists.
+    // At the top, the fetches issued NSTG - 1 tiles ago (V of this tile, K of the next) must
+    // have landed; younger ones may still be in flight.
+#define ATT_TILE(BUF, HAS_NEXT)                                                            \
     {                                                                                      \
-        ATT_FETCH_ALL(kt + 1, 1 - BUFC)                                                    \
-        if (kt + 2 < ntile) { ATT_ROWS(kt + 2) }                                           \
-        if (wave_active) compute_tile(std::false_type{}, std::integral_constant<int, BUFC>{}, ATT_BN); \
-        __builtin_amdgcn_s_waitcnt(0x0F70);     /* vmcnt(0): the next tile is in LDS */    \
+        if (NSTG > 2 && kt + NSTG - 1 < ntile) __builtin_amdgcn_s_waitcnt(0x0F70 | ((NSTG - 2) * 2 * NPASS)); \
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
         __syncthreads();                                                                   \
+        if (HAS_NEXT) {                                                                    \
+            if (kt + NSTG - 1 < ntile) { ATT_FETCH(off_nx, Vb, ld_voff, sV + ((BUF + NSTG - 1) % NSTG) * TILE_B) } \
+            if (kt + NSTG < ntile) {                                                       \
+                ATT_OFFS(kt + NSTG, off_nx)                                                \
+                ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
+            }                                                                              \
+            if (kt + NSTG + 1 < ntile) { ATT_ROWS(kt + NSTG + 1) }                         \
+        }                                                                                  \
+        if (wave_active) {                                                                 \
+            using HN = std::integral_constant<bool, HAS_NEXT>;                             \
+            constexpr int KB_ = ((BUF + 1) % NSTG) * TILE_B, VB_ = NSTG * TILE_B + BUF * TILE_B; \
+            phase_a(T{}, std::integral_constant<int, VB_>{}, s1, s0, pw0);                 \
+            if (!HAS_NEXT) mask_block(s1, 32, L - kt * ATT_BN);                            \
+            phase_b(T{}, HN{}, std::integral_constant<int, KB_>{}, pw0, s1, pw1);          \
+            phase_a(HN{}, std::integral_constant<int, VB_ + 32 * RB>{}, s0, s1, pw1);      \
+            if (HAS_NEXT && kt + 2 == ntile && L - (kt + 1) * ATT_BN < 32)                 \
+                mask_block(s0, 0, L - (kt + 1) * ATT_BN);                                  \
+            phase_b(HN{}, HN{}, std::integral_constant<int, KB_ + 32 * RB>{}, pw1, s0, pw0); \
+        }                                                                                  \
         ++kt;                                                                              \
     }
+    static_assert(NSTG == 2 || NSTG == 3, "the tile loop is unrolled by the number of buffers");
     int kt = 0;
-    while (kt < ntile - 1) {                    // every tile but the last: full, and a next one to fetch
-        ATT_STEP(0)
+    while (kt < ntile - 1) {                    // every tile but the last
+        ATT_TILE(0, true)
         if (kt >= ntile - 1) break;
-        ATT_STEP(1)
-    }
-    // the last tile (kept out of the loop so the loop body has a single path): maybe ragged
-    if (ntile > 0 && wave_active) {
-        const int rem = L - kt * ATT_BN;
-        if (kt & 1) {
-            if (rem < ATT_BN) compute_tile(std::true_type{}, std::integral_constant<int, 1>{}, rem);
-            else compute_tile(std::false_type{}, std::integral_constant<int, 1>{}, ATT_BN);
-        } else {
-            if (rem < ATT_BN) compute_tile(std::true_type{}, std::integral_constant<int, 0>{}, rem);
-            else compute_tile(std::false_type{}, std::integral_constant<int, 0>{}, ATT_BN);
+        ATT_TILE(1, true)
+        if constexpr (NSTG == 3) {
+            if (kt >= ntile - 1) break;
+            ATT_TILE((NSTG - 1), true)
         }
     }
-#undef ATT_STEP
-
-#undef ATT_NEW_MAX
+    if (ntile > 0) {                            // the last tile: nothing follows it, maybe ragged
+        const int bl = kt % NSTG;
+        if (bl == 0) ATT_TILE(0, false)
+        else if (bl == 1) ATT_TILE(1, false)
+        else if constexpr (NSTG == 3) ATT_TILE((NSTG - 1), false)
+    }
+#undef ATT_TILE
+#undef ATT_FENCE
+#undef ATT_PIN
 #undef ATT_ROWS
+#undef ATT_OFFS
 #undef ATT_FETCH
-#undef ATT_FETCH_ALL
 
     // ---- epilogue: normalise, store at the original row
     {
@@ -631,7 +703,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
 }
 
 // ---------------------------------------------------------------- host side
-static int attn_bm(int dtype) { return dtype == SVG2_BF16 ? 128 : 64; }   // rows per tile
+static int attn_bm(int dtype) { return dtype == SVG2_BF16 ? 32 * ATT_NW : 64; }   // rows per tile
 
 size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
 {
@@ -698,19 +770,19 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
-        const size_t lds = (size_t)4 * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
+        const size_t lds = (size_t)2 * ATT_NSTG * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
                            (size_t)(Ck + 1) * sizeof(int2);
         if (d == 128) {
             auto kern = attn_bf16_kernel<128>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
+            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
                                tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         } else {
             auto kern = attn_bf16_kernel<64>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(256), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
+            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
                                tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         }
     } else {
