@@ -20,6 +20,8 @@
 //
 // For bf16 input the assign step sees the centroids rounded to bf16 (both in
 // x.c and in ||c||^2); the centroids handed back stay fp32 means.
+#include <type_traits>
+
 #include "svg2_common.h"
 
 namespace svg2 {
@@ -27,9 +29,11 @@ namespace svg2 {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-static constexpr int KM_CT = 128;      // centroids staged in LDS per step (bf16 kernel)
-static constexpr int KM_TB = 4;        // 32-token blocks per wavefront (bf16 kernel)
-static constexpr int KM_WG_TOKENS = 4 * KM_TB * 32;
+static constexpr int KM_CMAX = 512;    // centroids resident in LDS at a time (bf16 kernel)
+static constexpr int KM_NW = 8;        // wavefronts per workgroup (bf16 kernel)
+static constexpr int KM_TB = 2;        // 32-token blocks per wavefront (bf16 kernel)
+static constexpr int KM_WG_TOKENS = KM_NW * KM_TB * 32;
+static constexpr int KM_IB = 8;        // token blocks per work item (bf16 kernel)
 static constexpr int KM_UB = 4;        // load instructions in flight per wavefront in the segmented sum
 static constexpr int KM_SEG = 256;     // rows per piece of the segmented sum
 
@@ -76,107 +80,168 @@ __global__ void kmeans_finalize_kernel(const float *__restrict__ init, float *__
 }
 
 // ---------------------------------------------------------------- assign, bf16 MFMA
+// grid (items, H), block 64 * KM_NW, one workgroup per CU.  A work item is KM_IB blocks of
+// KM_WG_TOKENS tokens of one head; the head's centroids (up to KM_CMAX at a time) stay in LDS
+// for the whole item.  argmin_j ||c_j||^2 - 2 x.c_j is taken as argmax_j x.c_j - ||c_j||^2 / 2:
+// the accumulators of the contraction start at -||c_j||^2 / 2 (the C operand of the first
+// matrix instruction), so no vector instruction is spent on forming the distance.  With more
+// than KM_CMAX centroids the running best of a token goes through `best_ws` between chunks.
 template <int D, bool OBJ>
-__global__ __launch_bounds__(256) void kmeans_assign_bf16_kernel(const bf16_t *__restrict__ X,
-                                                                 const bf16_t *__restrict__ cb,
-                                                                 const float *__restrict__ cn, int N, int C,
-                                                                 int32_t *__restrict__ labels,
-                                                                 float *__restrict__ objective, int obj_stride)
+__global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(
+    const bf16_t *__restrict__ X, const bf16_t *__restrict__ cb, const float *__restrict__ cn, int N, int C,
+    int32_t *__restrict__ labels, float *__restrict__ best_ws, float *__restrict__ objective, int obj_stride)
 {
     constexpr int KS = D / 16;              // MFMA k-steps
     constexpr int ROW = D + 8;              // LDS row stride in elements (16 bytes of padding)
-    __shared__ __align__(16) bf16_t s_c[KM_CT * ROW];
-    __shared__ float s_cn[KM_CT];
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    bf16_t *s_c = reinterpret_cast<bf16_t *>(s_raw);                           // [KM_CMAX][ROW]
+    float *s_hcn = reinterpret_cast<float *>(s_raw + (size_t)KM_CMAX * ROW * 2);   // [KM_CMAX]: -||c||^2 / 2
 
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
     const bf16_t *Xh = X + (size_t)h * N * D;
     const bf16_t *cbh = cb + (size_t)h * C * D;
     const float *cnh = cn + (size_t)h * C;
-    const int tok0 = blockIdx.x * KM_WG_TOKENS + wave * (KM_TB * 32);
+    const int nchunk = (C + KM_CMAX - 1) / KM_CMAX;
+    float obj = 0.f;
 
-    // tokens as the B operand: lane (col, half) holds elements 16 s + 8 half .. + 8 of token `col`
-    bf16x8 xb[KM_TB][KS];
-    float xx[KM_TB];
-#pragma unroll
-    for (int tb = 0; tb < KM_TB; ++tb) {
-        const int n = min(N - 1, tok0 + tb * 32 + col);
-        const uint4 *src = reinterpret_cast<const uint4 *>(Xh + (size_t)n * D + 8 * half);
-        xx[tb] = 0.f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const uint4 v = src[2 * s];
-            __builtin_memcpy(&xb[tb][s], &v, 16);
-            if (OBJ) {
-                const unsigned w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xFFFF0000u);
-                    xx[tb] = fmaf(lo, lo, xx[tb]);
-                    xx[tb] = fmaf(hi, hi, xx[tb]);
-                }
-            }
-        }
-    }
-
-    float best[KM_TB];
-    int bidx[KM_TB];
-#pragma unroll
-    for (int tb = 0; tb < KM_TB; ++tb) { best[tb] = INFINITY; bidx[tb] = 0; }
-
-    for (int c0 = 0; c0 < C; c0 += KM_CT) {
+    for (int chunk = 0; chunk < nchunk; ++chunk) {
+        const int c0 = chunk * KM_CMAX;
+        const int cc = min(KM_CMAX, C - c0), ccp = (cc + 31) & ~31;
         __syncthreads();
-        // stage KM_CT centroids (rows past C are zero with an infinite norm)
-        for (int e = tid; e < KM_CT * (D / 8); e += 256) {
+        // stage the chunk (rows past the last centroid are zero and can never win)
+        for (int e = tid; e < ccp * (D / 8); e += 64 * KM_NW) {
             const int r = e / (D / 8), part = e % (D / 8);
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (c0 + r < C) v = reinterpret_cast<const uint4 *>(cbh + (size_t)(c0 + r) * D)[part];
+            if (r < cc) v = reinterpret_cast<const uint4 *>(cbh + (size_t)(c0 + r) * D)[part];
             *reinterpret_cast<uint4 *>(&s_c[r * ROW + part * 8]) = v;
         }
-        if (tid < KM_CT) s_cn[tid] = (c0 + tid < C) ? cnh[c0 + tid] : INFINITY;
+        for (int t = tid; t < ccp; t += 64 * KM_NW) s_hcn[t] = (t < cc) ? -0.5f * cnh[c0 + t] : -INFINITY;
         __syncthreads();
-        const int nrb = min(KM_CT / 32, (C - c0 + 31) / 32);
-        for (int rb = 0; rb < nrb; ++rb) {
-            f32x16 acc[KM_TB];
+
+        // Token blocks of the item, two register buffers: the tokens of block b + 1 are requested
+        // from global memory before block b is computed.
+        // tokens as the B operand: lane (col, half) holds elements 16 s + 8 half .. + 8 of token `col`
+        bf16x8 xb[2][KM_TB][KS];
+        const int blk0 = blockIdx.x * KM_IB;
+        auto load_x = [&](auto buf_tag, int b) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            const int tok0 = (blk0 + b) * KM_WG_TOKENS + wave * (KM_TB * 32);
 #pragma unroll
-            for (int tb = 0; tb < KM_TB; ++tb)
+            for (int tb = 0; tb < KM_TB; ++tb) {
+                const int n = min(N - 1, tok0 + tb * 32 + col);
+                const uint4 *src = reinterpret_cast<const uint4 *>(Xh + (size_t)n * D + 8 * half);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[tb][i] = 0.f;
-            const bf16_t *arow = &s_c[(rb * 32 + col) * ROW + 8 * half];
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                bf16x8 a;
-                const uint4 v = *reinterpret_cast<const uint4 *>(arow + 16 * s);
-                __builtin_memcpy(&a, &v, 16);
-#pragma unroll
-                for (int tb = 0; tb < KM_TB; ++tb)
-                    acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xb[tb][s], acc[tb], 0, 0, 0);
-            }
-            // accumulator i of a lane is centroid rb*32 + 8 (i/4) + 4 half + i%4: ascending in i
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = rb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                const float cnv = s_cn[r];
-#pragma unroll
-                for (int tb = 0; tb < KM_TB; ++tb) {
-                    const float dist = fmaf(-2.f, acc[tb][i], cnv);
-                    if (dist < best[tb]) { best[tb] = dist; bidx[tb] = c0 + r; }
+                for (int s = 0; s < KS; ++s) {
+                    const uint4 v = src[2 * s];
+                    __builtin_memcpy(&xb[BUF][tb][s], &v, 16);
                 }
             }
-        }
-    }
-
-    float obj = 0.f;
+        };
+        // One step = one 32-centroid row block against the wavefront's KM_TB token blocks: KS * KM_TB
+        // matrix instructions back to back, then the argmax of their accumulators on the vector ALU
+        // while the other wavefront of the SIMD has the matrix cores.  The operands of the next step
+        // (centroid rows, -||c||^2 / 2) are requested from LDS before the argmax.  argmax of a step:
+        // m = max of the 16 accumulators (max3 chain), the offset of the first accumulator equal to m,
+        // then one compare with the running best.
+        auto compute = [&](auto buf_tag, int b) {
+            constexpr int BUF = decltype(buf_tag)::value;
+            const int tok0 = (blk0 + b) * KM_WG_TOKENS + wave * (KM_TB * 32);
+            float best[KM_TB];
+            int bidx[KM_TB];
 #pragma unroll
-    for (int tb = 0; tb < KM_TB; ++tb) {
-        const float ob = __shfl_xor(best[tb], 32);
-        const int oi = __shfl_xor(bidx[tb], 32);
-        if (ob < best[tb] || (ob == best[tb] && oi < bidx[tb])) { best[tb] = ob; bidx[tb] = oi; }
-        const int n = tok0 + tb * 32 + col;
-        if (half == 0 && n < N) labels[(size_t)h * N + n] = bidx[tb];
-        if (OBJ) {
-            const float x2 = xx[tb] + __shfl_xor(xx[tb], 32);
-            if (half == 0 && n < N) obj += x2 + best[tb];
+            for (int tb = 0; tb < KM_TB; ++tb) {
+                if (chunk == 0) {
+                    best[tb] = -INFINITY;
+                    bidx[tb] = 0;
+                } else {
+                    const int n = min(N - 1, tok0 + tb * 32 + col);
+                    best[tb] = best_ws[(size_t)h * N + n];
+                    bidx[tb] = labels[(size_t)h * N + n];
+                }
+            }
+            const int nrb = ccp / 32;
+            bf16x8 a[KS];
+            f32x16 cinit;
+            auto fetch = [&](int rb) {          // accumulator i is centroid 8 (i/4) + 4 half + i%4 of the row block
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 v = *reinterpret_cast<const float4 *>(&s_hcn[rb * 32 + 8 * g + 4 * half]);
+                    cinit[4 * g] = v.x; cinit[4 * g + 1] = v.y; cinit[4 * g + 2] = v.z; cinit[4 * g + 3] = v.w;
+                }
+                const bf16_t *arow = &s_c[(rb * 32 + col) * ROW + 8 * half];
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(arow + 16 * s);
+                    __builtin_memcpy(&a[s], &v, 16);
+                }
+            };
+            fetch(0);
+#pragma unroll 1
+            for (int rb = 0; rb < nrb; ++rb) {
+                f32x16 acc[KM_TB];
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+#pragma unroll
+                    for (int q = 0; q < KM_TB; ++q)
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], xb[BUF][q][s], s == 0 ? cinit : acc[q], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rb + 1 < nrb) fetch(rb + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const int rbase = c0 + rb * 32 + 4 * half;
+#pragma unroll
+                for (int q = 0; q < KM_TB; ++q) {
+                    float m = fmaxf(fmaxf(acc[q][0], acc[q][1]), acc[q][2]);
+#pragma unroll
+                    for (int c = 1; c < 7; ++c) m = fmaxf(fmaxf(m, acc[q][2 * c + 1]), acc[q][2 * c + 2]);
+                    m = fmaxf(m, acc[q][15]);
+                    int off = 0;
+#pragma unroll
+                    for (int i = 15; i >= 0; --i)               // descending: a tie keeps the lower centroid
+                        off = (acc[q][i] == m) ? 8 * (i >> 2) + (i & 3) : off;
+                    const bool upd = m > best[q];                 // strict: a tie keeps the earlier row block
+                    best[q] = upd ? m : best[q];
+                    bidx[q] = upd ? rbase + off : bidx[q];
+                    // the values have to exist here: keeps the argmax in front of the next contraction
+                    asm volatile("" : "+v"(best[q]), "+v"(bidx[q]));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int tb = 0; tb < KM_TB; ++tb) {
+                const float ob = __shfl_xor(best[tb], 32);
+                const int oi = __shfl_xor(bidx[tb], 32);
+                if (ob > best[tb] || (ob == best[tb] && oi < bidx[tb])) { best[tb] = ob; bidx[tb] = oi; }
+                const int n = tok0 + tb * 32 + col;
+                if (half == 0 && n < N) {
+                    labels[(size_t)h * N + n] = bidx[tb];
+                    if (chunk + 1 < nchunk) best_ws[(size_t)h * N + n] = best[tb];
+                }
+                if (OBJ && chunk + 1 == nchunk) {
+                    float x2 = 0.f;                               // ||x||^2 of this lane's half of the token
+#pragma unroll
+                    for (int s = 0; s < KS; ++s)
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const float xv = (float)xb[BUF][tb][s][k];
+                            x2 = fmaf(xv, xv, x2);
+                        }
+                    x2 += __shfl_xor(x2, 32);
+                    if (half == 0 && n < N) obj += x2 - 2.f * best[tb];
+                }
+            }
+        };
+        // blocks of this item that hold tokens (wavefront-uniform)
+        const int nblk = min(KM_IB, (N - blk0 * KM_WG_TOKENS + KM_WG_TOKENS - 1) / KM_WG_TOKENS);
+        if (nblk > 0) load_x(std::integral_constant<int, 0>{}, 0);
+#pragma unroll 1
+        for (int b = 0; b < nblk; b += 2) {
+            if (b + 1 < nblk) load_x(std::integral_constant<int, 1>{}, b + 1);
+            compute(std::integral_constant<int, 0>{}, b);
+            if (b + 1 < nblk) {
+                if (b + 2 < nblk) load_x(std::integral_constant<int, 0>{}, b + 2);
+                compute(std::integral_constant<int, 1>{}, b + 1);
+            }
         }
     }
     if (OBJ) {
@@ -354,7 +419,7 @@ struct KmeansWs {
     float *cn;
     int32_t *offsets, *perm, *first_piece, *n_pieces;
     int4 *pieces;
-    float *psum;
+    float *psum, *best;
     void *sort_ws;
     int max_pieces;
     size_t total;
@@ -373,6 +438,7 @@ static KmeansWs kmeans_carve(void *ws, int H, int N, int d, int C)
     k.n_pieces = c.take<int32_t>((size_t)H);
     k.pieces = c.take<int4>((size_t)H * k.max_pieces);
     k.psum = c.take<float>((size_t)H * k.max_pieces * d);
+    k.best = c.take<float>(C > KM_CMAX ? (size_t)H * N : 0);
     k.sort_ws = c.take<char>(permute_ws_bytes(H, N, C));
     k.total = c.used;
     return k;
@@ -396,14 +462,13 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
     for (int t = 0; t < iters; ++t) {
         float *obj = objective ? objective + t : nullptr;
         if (BF16) {
-            const dim3 grid(cdiv(N, KM_WG_TOKENS), H);
+            const dim3 grid(cdiv(cdiv(N, KM_WG_TOKENS), KM_IB), H);
             const bf16_t *Xb = reinterpret_cast<const bf16_t *>(X);
-            if (obj)
-                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, true>), grid, dim3(256), 0, st, Xb, k.cb, k.cn, N, C,
-                                   labels, obj, iters);
-            else
-                hipLaunchKernelGGL((kmeans_assign_bf16_kernel<D, false>), grid, dim3(256), 0, st, Xb, k.cb, k.cn, N, C,
-                                   labels, obj, iters);
+            const size_t lds = (size_t)KM_CMAX * (D + 8) * sizeof(bf16_t) + KM_CMAX * sizeof(float);
+            auto kern = obj ? kmeans_assign_bf16_kernel<D, true> : kmeans_assign_bf16_kernel<D, false>;
+            SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL(kern, grid, dim3(64 * KM_NW), lds, st, Xb, k.cb, k.cn, N, C, labels, k.best, obj, iters);
         } else {
             const dim3 grid(cdiv(N, 128), H);
             const float *Xf = reinterpret_cast<const float *>(X);

@@ -171,7 +171,9 @@ def test_kmeans_small_bf16(svg2, oracle, iters):
 
 
 @pytest.mark.parametrize("dtype,d,N,C", [("bf16", 64, 1000, 33), ("f32", 128, 777, 50), ("bf16", 128, 513, 513),
-                                         ("bf16", 128, 700, 1), ("f32", 64, 300, 300)])
+                                         ("bf16", 128, 700, 1), ("f32", 64, 300, 300),
+                                         # more centroids than the LDS holds at once, several token blocks per item
+                                         ("bf16", 128, 5000, 1000), ("bf16", 64, 4500, 1100)])
 def test_kmeans_ragged_shapes(svg2, oracle, dtype, d, N, C):
     r = np.random.default_rng(300 + N)
     X = r.standard_normal((2, N, d)).astype(np.float32) + 2.0 * r.standard_normal((2, 1, d)).astype(np.float32)
