@@ -123,6 +123,8 @@ def main():
     ap.add_argument("--iters", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--gather-free", action="store_true",
+                    help="time svg2_forward_gather_free (no permuted copies of Q, K, V) instead of svg2_forward")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -166,11 +168,13 @@ def main():
     cqs = [cq0.clone() for _ in range(total + 1)]
     cks = [ck0.clone() for _ in range(total + 1)]
     O = torch.empty_like(Q)
-    ws = torch.empty(svg2.svg2_forward_workspace_size(svg2.SVG2_BF16, H, N, d, w.Cq, w.Ck), dtype=torch.uint8,
-                     device="cuda")
+    ws = torch.empty(svg2.svg2_forward_workspace_size(svg2.SVG2_BF16, H, N, d, w.Cq, w.Ck, args.gather_free),
+                     dtype=torch.uint8, device="cuda")
+    log("workspace %.2f GB (%s)" % (ws.numel() / 1e9, "gather-free" if args.gather_free else "physical permutation"))
 
     def step(i, aux=False):
-        return svg2.svg2_forward(Q, K, V, cqs[i], cks[i], w.top_p, w.iters, out=O, ws=ws, want_aux=aux)
+        return svg2.svg2_forward(Q, K, V, cqs[i], cks[i], w.top_p, w.iters, out=O, ws=ws, want_aux=aux,
+                                 gather_free=args.gather_free)
 
     r = step(total, aux=True)                 # an extra, untimed pass that also reports the density
     torch.cuda.synchronize()
@@ -204,7 +208,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "H": H, "N": N, "d": d, "Cq": w.Cq, "Ck": w.Ck, "kmeans_iters": w.iters,
-                   "top_p": w.top_p, "density": float(density.mean())},
+                   "top_p": w.top_p, "density": float(density.mean()),
+                   "entry_point": "svg2_forward_gather_free" if args.gather_free else "svg2_forward"},
         "stages_ms": stage_ms,
         "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": achieved,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
@@ -216,11 +221,12 @@ def main():
         one = torch.tensor([[0, N]] * H, dtype=torch.int32, device="cuda")
         rp = torch.tensor([[0, 1]] * H, dtype=torch.int32, device="cuda")
         ci = torch.zeros((H, 1), dtype=torch.int32, device="cuda")
-        svg2.svg2_sparse_attn(Q, K, V, one, one, rp, ci, None, out=O, ws=ws)
+        wsd = ws if not args.gather_free else None   # (the gather-free workspace may be smaller than this call needs)
+        svg2.svg2_sparse_attn(Q, K, V, one, one, rp, ci, None, out=O, ws=wsd)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        svg2.svg2_sparse_attn(Q, K, V, one, one, rp, ci, None, out=O, ws=ws)
+        svg2.svg2_sparse_attn(Q, K, V, one, one, rp, ci, None, out=O, ws=wsd)
         e1.record()
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1)

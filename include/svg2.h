@@ -147,6 +147,24 @@ int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype,
                      void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * svg2_sparse_attn_gather_free -- Section 4.3 as the paper describes its own
+ * kernel: keys and values are loaded sparsely, token by token, and computed
+ * densely, so no permuted copy of Q, K or V exists.  Same result as
+ * svg2_sparse_attn on the permuted copies.
+ *   Q, K, V [H,N,d] dtype             in ORIGINAL token order
+ *   perm_q, perm_k [H,N] int32        both required (svg2_permute's perm)
+ *   every other argument as in svg2_sparse_attn; O is in original token order.
+ * Workspace: svg2_sparse_attn_workspace_size.
+ * ------------------------------------------------------------------------- */
+int svg2_sparse_attn_gather_free(const void *Q, const void *K, const void *V, int dtype,
+                                 int H, int N, int d, int Cq, int Ck,
+                                 const int32_t *offsets_q, const int32_t *offsets_k,
+                                 const int32_t *row_ptr, const int32_t *col_idx,
+                                 const int32_t *perm_q, const int32_t *perm_k,
+                                 float scale, void *O, float *lse,
+                                 void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * svg2_forward -- the whole layer (Section 4): k-means of Q and of K,
  * both permutations, selection, sparse attention, output in original order.
  *   Q, K, V [H,N,d] dtype; O [H,N,d] dtype out
@@ -177,6 +195,20 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype,
                  float *cq_inout, float *ck_inout, void *O,
                  const svg2_forward_aux *aux,
                  void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_forward_gather_free -- svg2_forward without the physical permutation of
+ * Q, K and V (Section 4.3, sparse loading): the permutations exist as index
+ * vectors only and the attention kernel fetches rows through them.  Same
+ * arguments and results as svg2_forward; the workspace is smaller by three
+ * [H,N,d] tensors.
+ * ------------------------------------------------------------------------- */
+size_t svg2_forward_gather_free_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck);
+int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dtype,
+                             int H, int N, int d, int Cq, int Ck, float top_p, int iters,
+                             float *cq_inout, float *ck_inout, void *O,
+                             const svg2_forward_aux *aux,
+                             void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Stage timing for benchmarks (HOST-side state, one per process).

@@ -27,8 +27,9 @@ EXPORTS = (
     "svg2_kmeans_workspace_size", "svg2_kmeans",
     "svg2_permute_workspace_size", "svg2_permute",
     "svg2_select_topp_workspace_size", "svg2_select_topp",
-    "svg2_sparse_attn_workspace_size", "svg2_sparse_attn",
+    "svg2_sparse_attn_workspace_size", "svg2_sparse_attn", "svg2_sparse_attn_gather_free",
     "svg2_forward_workspace_size", "svg2_forward",
+    "svg2_forward_gather_free_workspace_size", "svg2_forward_gather_free",
     "svg2_profile_enable", "svg2_profile_read",
 )
 STAGES = ("kmeans_q", "kmeans_k", "permute", "select", "attn_plan", "attn")
@@ -72,8 +73,12 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_select_topp.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, vp, vp, vp, sz, vp]
         lib.svg2_sparse_attn_workspace_size.argtypes = [i, i, i, i, i, i]
         lib.svg2_sparse_attn.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, f, vp, vp, vp, sz, vp]
+        lib.svg2_sparse_attn_gather_free.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, f, vp, vp, vp,
+                                                     sz, vp]
         lib.svg2_forward_workspace_size.argtypes = [i, i, i, i, i, i]
         lib.svg2_forward.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, vp, sz, vp]
+        lib.svg2_forward_gather_free_workspace_size.argtypes = [i, i, i, i, i, i]
+        lib.svg2_forward_gather_free.argtypes = lib.svg2_forward.argtypes
         lib.svg2_profile_enable.argtypes = [i]
         lib.svg2_profile_read.argtypes = [vp, vp]
         _lib = lib
@@ -201,11 +206,42 @@ def svg2_sparse_attn(Qp, Kp, Vp, offsets_q, offsets_k, row_ptr, col_idx, perm_q=
     return SimpleNamespace(O=O, lse=lse)
 
 
-def svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck) -> int:
-    return load_library().svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck)
+def svg2_sparse_attn_gather_free(Q, K, V, offsets_q, offsets_k, row_ptr, col_idx, perm_q, perm_k, *, scale=0.0,
+                                 want_lse=False, out=None, ws=None):
+    """Section 4.3 with sparse loading: Q, K, V [H,N,d] in token order + both permutations + block list -> O."""
+    lib = load_library()
+    H, N, d = Q.shape
+    Cq, Ck = offsets_q.shape[1] - 1, offsets_k.shape[1] - 1
+    dt = _dtype_code(Q)
+    dev = Q.device
+    if col_idx.numel() < H * Cq * Ck:
+        raise ValueError("col_idx must have capacity H*Cq*Ck")
+    O = torch.empty_like(Q) if out is None else out
+    lse = torch.empty((H, N), dtype=torch.float32, device=dev) if want_lse else None
+    need = lib.svg2_sparse_attn_workspace_size(dt, H, N, d, Cq, Ck)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_sparse_attn_gather_free(
+        _dev(Q, name="Q"), _dev(K, Q.dtype, "K"), _dev(V, Q.dtype, "V"), dt, H, N, d, Cq, Ck,
+        _dev(offsets_q, torch.int32, "offsets_q"), _dev(offsets_k, torch.int32, "offsets_k"),
+        _dev(row_ptr, torch.int32, "row_ptr"), _dev(col_idx, torch.int32, "col_idx"),
+        _dev(perm_q, torch.int32, "perm_q"), _dev(perm_k, torch.int32, "perm_k"), float(scale),
+        _dev(O, Q.dtype, "O"), _dev(lse), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(O=O, lse=lse)
 
 
-def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, out=None, ws=None):
+def svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck, gather_free=False) -> int:
+    lib = load_library()
+    fn = lib.svg2_forward_gather_free_workspace_size if gather_free else lib.svg2_forward_workspace_size
+    return fn(dtype_code, H, N, d, Cq, Ck)
+
+
+def svg2_forward_gather_free(Q, K, V, cq_inout, ck_inout, top_p, iters, **kw):
+    """svg2_forward without permuted copies of Q, K, V (Section 4.3, sparse loading)."""
+    return svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, gather_free=True, **kw)
+
+
+def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, out=None, ws=None,
+                 gather_free=False):
     """Section 4, the whole layer.  cq_inout / ck_inout [H,C,d] fp32 are updated in place (centroid cache)."""
     lib = load_library()
     H, N, d = Q.shape
@@ -227,9 +263,10 @@ def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, o
             lse=torch.empty((H, N), dtype=torch.float32, device=dev))
         aux_s = _ForwardAux(**{n: getattr(aux_t, n).data_ptr() for n, _ in _ForwardAux._fields_})
         aux_p = ctypes.cast(ctypes.pointer(aux_s), ctypes.c_void_p)
-    need = lib.svg2_forward_workspace_size(dt, H, N, d, Cq, Ck)
+    need = svg2_forward_workspace_size(dt, H, N, d, Cq, Ck, gather_free)
     ws = _workspace(need, dev) if ws is None else ws
-    _check(lib.svg2_forward(_dev(Q, name="Q"), _dev(K, Q.dtype, "K"), _dev(V, Q.dtype, "V"), dt, H, N, d, Cq, Ck,
+    entry = lib.svg2_forward_gather_free if gather_free else lib.svg2_forward
+    _check(entry(_dev(Q, name="Q"), _dev(K, Q.dtype, "K"), _dev(V, Q.dtype, "V"), dt, H, N, d, Cq, Ck,
                             float(top_p), int(iters), _dev(cq_inout, torch.float32, "cq_inout"),
                             _dev(ck_inout, torch.float32, "ck_inout"), _dev(O, Q.dtype, "O"), aux_p,
                             _dev(ws), ws.numel(), _stream()))

@@ -64,7 +64,8 @@ struct ForwardLayout {
     size_t stage_bytes, total;
 };
 
-static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, int Cq, int Ck)
+// gather_free: no permuted copies of Q, K, V (the attention kernel reads rows through the permutations)
+static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, int Cq, int Ck, bool gather_free)
 {
     ForwardLayout L;
     Carver c(ws);
@@ -80,9 +81,9 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     L.row_ptr = c.take<int32_t>((size_t)H * (Cq + 1));
     L.col_idx = c.take<int32_t>((size_t)H * Cq * Ck);
     L.density = c.take<float>((size_t)H);
-    L.Qp = c.take<char>((size_t)H * N * d * es);
-    L.Kp = c.take<char>((size_t)H * N * d * es);
-    L.Vp = c.take<char>((size_t)H * N * d * es);
+    L.Qp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
+    L.Kp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
+    L.Vp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
     // the stages run one after another on one stream and share one scratch area
     size_t s = kmeans_ws_bytes(dtype, H, N, d, Cq);
     size_t t = kmeans_ws_bytes(dtype, H, N, d, Ck);
@@ -231,8 +232,26 @@ int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype, 
                  "Qp, Kp, Vp, O, offsets_q, offsets_k, row_ptr and col_idx must be non-null");
     SVG2_REQUIRE(O != Qp && O != Kp && O != Vp, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(dtype, H, N, d, Cq, Ck)));
-    return attn_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, scale, O,
-                       lse, ws, static_cast<hipStream_t>(stream));
+    return attn_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, nullptr,
+                       scale, O, lse, ws, static_cast<hipStream_t>(stream));
+}
+
+int svg2_sparse_attn_gather_free(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq,
+                                 int Ck, const int32_t *offsets_q, const int32_t *offsets_k, const int32_t *row_ptr,
+                                 const int32_t *col_idx, const int32_t *perm_q, const int32_t *perm_k, float scale,
+                                 void *O, float *lse, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_clusters("Cq", Cq, N));
+    SVG2_TRY(check_clusters("Ck", Ck, N));
+    SVG2_REQUIRE(Q && K && V && O && offsets_q && offsets_k && row_ptr && col_idx && perm_q && perm_k,
+                 SVG2_INVALID_ARG,
+                 "Q, K, V, O, offsets_q, offsets_k, row_ptr, col_idx, perm_q and perm_k must be non-null");
+    SVG2_REQUIRE(O != Q && O != K && O != V, SVG2_INVALID_ARG, "O must not alias an input");
+    SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(dtype, H, N, d, Cq, Ck)));
+    return attn_launch(Q, K, V, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, perm_k, scale,
+                       O, lse, ws, static_cast<hipStream_t>(stream));
 }
 
 size_t svg2_forward_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
@@ -240,12 +259,22 @@ size_t svg2_forward_workspace_size(int dtype, int H, int N, int d, int Cq, int C
     if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("Cq", Cq, N) != SVG2_OK ||
         check_clusters("Ck", Ck, N) != SVG2_OK)
         return 256;
-    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck).total;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, false).total;
 }
 
-int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
-                 float top_p, int iters, float *cq_inout, float *ck_inout, void *O, const svg2_forward_aux *aux,
-                 void *ws, size_t ws_bytes, void *stream)
+size_t svg2_forward_gather_free_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
+{
+    if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("Cq", Cq, N) != SVG2_OK ||
+        check_clusters("Ck", Ck, N) != SVG2_OK)
+        return 256;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, true).total;
+}
+
+}  // extern "C"
+
+static int forward_impl(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
+                        float top_p, int iters, float *cq_inout, float *ck_inout, void *O,
+                        const svg2_forward_aux *aux, void *ws, size_t ws_bytes, void *stream, bool gather_free)
 {
     clear_error();
     SVG2_TRY(check_common(dtype, H, N, d));
@@ -257,7 +286,7 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
                  "Q, K, V, O, cq_inout and ck_inout must be non-null");
     SVG2_REQUIRE(O != Q && O != K && O != V, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_REQUIRE(ws != nullptr, SVG2_INVALID_ARG, "workspace pointer is null");
-    ForwardLayout L = forward_layout(ws, dtype, H, N, d, Cq, Ck);
+    ForwardLayout L = forward_layout(ws, dtype, H, N, d, Cq, Ck, gather_free);
     SVG2_TRY(check_ws(ws, ws_bytes, L.total));
     float *lse = nullptr;
     if (aux) {
@@ -285,14 +314,15 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
                            L.stage_ws, st));
     profile_mark(pb, 2, st);
     // Section 4.1: permutations; K and V share pi_k
+    // (gather-free: only the index vectors; the rows are fetched through them in the attention kernel)
     const void *src_q[1] = {Q};
     void *dst_q[1] = {L.Qp};
-    SVG2_TRY(permute_launch(L.labels_q, H, N, Cq, L.offsets_q, L.perm_q, nullptr, 1, src_q, dst_q, dtype, d,
-                            L.stage_ws, st));
+    SVG2_TRY(permute_launch(L.labels_q, H, N, Cq, L.offsets_q, L.perm_q, nullptr, gather_free ? 0 : 1, src_q, dst_q,
+                            dtype, d, L.stage_ws, st));
     const void *src_k[2] = {K, V};
     void *dst_k[2] = {L.Kp, L.Vp};
-    SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, 2, src_k, dst_k, dtype, d,
-                            L.stage_ws, st));
+    SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, gather_free ? 0 : 2, src_k, dst_k,
+                            dtype, d, L.stage_ws, st));
     profile_mark(pb, 3, st);
     // Section 4.2: which (query cluster, key cluster) pairs to compute
     SVG2_TRY(select_launch(cq_inout, ck_inout, L.counts_q, L.counts_k, H, Cq, Ck, d, top_p, L.row_ptr, L.col_idx,
@@ -301,10 +331,32 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
     // Section 4.3: attention over the selected pairs, result back in token order
     SVG2_TRY(attn_plan_launch(dtype, H, N, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx, L.stage_ws, st));
     profile_mark(pb, 5, st);
-    SVG2_TRY(attn_main_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, 0.f, O, lse, L.stage_ws,
-                              st));
+    if (gather_free)
+        SVG2_TRY(attn_main_launch(Q, K, V, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, L.perm_k, 0.f, O, lse,
+                                  L.stage_ws, st));
+    else
+        SVG2_TRY(attn_main_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, nullptr, 0.f, O, lse,
+                                  L.stage_ws, st));
     profile_mark(pb, 6, st);
     return SVG2_OK;
+}
+
+extern "C" {
+
+int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
+                 float top_p, int iters, float *cq_inout, float *ck_inout, void *O, const svg2_forward_aux *aux,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    return forward_impl(Q, K, V, dtype, H, N, d, Cq, Ck, top_p, iters, cq_inout, ck_inout, O, aux, ws, ws_bytes,
+                        stream, false);
+}
+
+int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq,
+                             int Ck, float top_p, int iters, float *cq_inout, float *ck_inout, void *O,
+                             const svg2_forward_aux *aux, void *ws, size_t ws_bytes, void *stream)
+{
+    return forward_impl(Q, K, V, dtype, H, N, d, Cq, Ck, top_p, iters, cq_inout, ck_inout, O, aux, ws, ws_bytes,
+                        stream, true);
 }
 
 int svg2_profile_enable(int enable)

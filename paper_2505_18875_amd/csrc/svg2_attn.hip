@@ -22,6 +22,10 @@
 //
 // The result of sorted row r is stored at row perm_q[r] (Section 4.1: the
 // inverse query permutation restores the original order).
+//
+// Gather-free variant (perm_k given): Q, K and V stay in token order and the
+// kernels go through perm_q / perm_k when they fetch a row -- the per-token
+// sparse load of Section 4.3 -- so no permuted copies are needed.
 #include <type_traits>
 
 #include "svg2_common.h"
@@ -218,7 +222,8 @@ template <int D>
 __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
-    const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base, int max_tiles,
+    const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
+    int max_tiles,
     const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2, int group,
     bf16_t *__restrict__ O, float *__restrict__ lse)
 {
@@ -276,7 +281,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     // ---- queries as the B operand of S^T = K Q^T: this wavefront owns 32 rows of the tile
     bf16x8 qreg[KS];
     {
-        const int r = row0 + min(nrows - 1, wave * 32 + col);
+        int r = row0 + min(nrows - 1, wave * 32 + col);
+        if (perm_k) r = perm_q[(size_t)h * N + r];      // gather-free: Q is in token order
         const uint4 *src = reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + 8 * half);
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -303,6 +309,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     // kept in registers from its K fetch to its V fetch.
     const char *Kb = reinterpret_cast<const char *>(Kh);
     const char *Vb = reinterpret_cast<const char *>(Vh);
+    const int32_t *pkh = perm_k ? perm_k + (size_t)h * N : nullptr;
     int cur = 0;
     const int ld_row = lane / CPR;                                  // row inside the instruction's group
     const int ld_swz = ((wave * RPI + ld_row) / (256 / RB));
@@ -313,7 +320,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #define ATT_ROWS(KT)                                                                       \
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
-        s_rows[((KT) & 1) * ATT_BN + lane] = (kk < L) ? run_lookup(s_run, cur, kk) : 0;    \
+        int row_ = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
+        if (perm_k) row_ = pkh[row_];           /* gather-free: sorted row -> token */     \
+        s_rows[((KT) & 1) * ATT_BN + lane] = row_;                                         \
     }
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
@@ -616,9 +625,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 template <int D>
 __global__ __launch_bounds__(64) void attn_f32_kernel(
     const float *__restrict__ Q, const float *__restrict__ K, const float *__restrict__ V, int N, int Cq, int Ck,
-    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q, const int4 *__restrict__ tiles,
-    const int32_t *__restrict__ n_tiles, int max_tiles, const int2 *__restrict__ runs,
-    const int32_t *__restrict__ row_keys, float scale, float *__restrict__ O, float *__restrict__ lse)
+    const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q, const int32_t *__restrict__ perm_k,
+    const int4 *__restrict__ tiles, const int32_t *__restrict__ n_tiles, int max_tiles,
+    const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale, float *__restrict__ O,
+    float *__restrict__ lse)
 {
     constexpr int TN = 32;
     __shared__ __align__(16) float sK[TN * D];
@@ -634,10 +644,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
     const float *Kh = K + (size_t)h * N * D, *Vh = V + (size_t)h * N * D;
 
     const int r = row0 + min(tid, nrows - 1);
+    const int qr = perm_k ? perm_q[(size_t)h * N + r] : r;      // gather-free: Q is in token order
     float q[D], o[D];
 #pragma unroll
     for (int k = 0; k < D / 4; ++k) {
-        const float4 w = reinterpret_cast<const float4 *>(Q + ((size_t)h * N + r) * D)[k];
+        const float4 w = reinterpret_cast<const float4 *>(Q + ((size_t)h * N + qr) * D)[k];
         q[4 * k] = w.x; q[4 * k + 1] = w.y; q[4 * k + 2] = w.z; q[4 * k + 3] = w.w;
     }
 #pragma unroll
@@ -653,7 +664,8 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
         if (kk < L) {
             while (cur + 1 < nnz && kk >= rn[cur + 1].y) ++cur;
             const int2 rs = rn[cur];
-            const size_t src = (size_t)(rs.x + kk - rs.y);
+            size_t src = (size_t)(rs.x + kk - rs.y);
+            if (perm_k) src = (size_t)perm_k[(size_t)h * N + src];  // gather-free: sorted row -> token
             const float4 *kp = reinterpret_cast<const float4 *>(Kh + src * D + hpart * (D / 2));
             const float4 *vp = reinterpret_cast<const float4 *>(Vh + src * D + hpart * (D / 2));
             float4 *dk = reinterpret_cast<float4 *>(sK + slot * D + hpart * (D / 2));
@@ -751,8 +763,8 @@ int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *off
 }
 
 int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
-                     const int32_t *row_ptr, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
-                     hipStream_t st)
+                     const int32_t *row_ptr, const int32_t *perm_q, const int32_t *perm_k, float scale, void *O,
+                     float *lse, void *ws, hipStream_t st)
 {
     const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
     const int max_tiles = a.max_tiles;
@@ -776,14 +788,14 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
             auto kern = attn_bf16_kernel<128>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
+            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
+                               tiles, tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         } else {
             auto kern = attn_bf16_kernel<64>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, tiles,
-                               tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
+            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
+                               tiles, tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         }
     } else {
         const float *q = static_cast<const float *>(Qp), *k = static_cast<const float *>(Kp),
@@ -791,10 +803,10 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         float *o = static_cast<float *>(O);
         if (d == 128)
             hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(max_tiles, H), dim3(64), 0, st, q, k, v, N, Cq, Ck, row_ptr,
-                               perm_q, tiles, n_tiles, max_tiles, runs, row_keys, scale, o, lse);
+                               perm_q, perm_k, tiles, n_tiles, max_tiles, runs, row_keys, scale, o, lse);
         else
             hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(max_tiles, H), dim3(64), 0, st, q, k, v, N, Cq, Ck, row_ptr,
-                               perm_q, tiles, n_tiles, max_tiles, runs, row_keys, scale, o, lse);
+                               perm_q, perm_k, tiles, n_tiles, max_tiles, runs, row_keys, scale, o, lse);
     }
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
@@ -802,12 +814,12 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
 
 int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
                 const int32_t *offsets_q, const int32_t *offsets_k, const int32_t *row_ptr,
-                const int32_t *col_idx, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
-                hipStream_t st)
+                const int32_t *col_idx, const int32_t *perm_q, const int32_t *perm_k, float scale, void *O,
+                float *lse, void *ws, hipStream_t st)
 {
     const int rc = attn_plan_launch(dtype, H, N, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, ws, st);
     if (rc != SVG2_OK) return rc;
-    return attn_main_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, row_ptr, perm_q, scale, O, lse, ws, st);
+    return attn_main_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, row_ptr, perm_q, perm_k, scale, O, lse, ws, st);
 }
 
 }  // namespace svg2

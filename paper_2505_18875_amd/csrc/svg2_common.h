@@ -86,14 +86,15 @@ int select_launch(const float *cq, const float *ck, const int32_t *counts_q, con
 size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck);
 int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d,
                 int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
-                const int32_t *row_ptr, const int32_t *col_idx, const int32_t *perm_q, float scale,
-                void *O, float *lse, void *ws, hipStream_t st);
+                const int32_t *row_ptr, const int32_t *col_idx, const int32_t *perm_q,
+                const int32_t *perm_k, float scale, void *O, float *lse, void *ws, hipStream_t st);
 
+// perm_k == nullptr: Qp, Kp, Vp are permuted copies; perm_k given: they are in token order (gather-free).
 // the two halves of attn_launch, separately (so a caller can time them)
 int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
                      const int32_t *row_ptr, const int32_t *col_idx, void *ws, hipStream_t st);
 int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d, int Cq, int Ck,
-                     const int32_t *row_ptr, const int32_t *perm_q, float scale, void *O, float *lse, void *ws,
-                     hipStream_t st);
+                     const int32_t *row_ptr, const int32_t *perm_q, const int32_t *perm_k, float scale, void *O,
+                     float *lse, void *ws, hipStream_t st);
 
 }  // namespace svg2

@@ -229,6 +229,14 @@ def _attn_case(oracle, svg2, Q, K, V, lq, lk, sel_rows, dtype, rows=None, tol=(2
     fin = np.isfinite(lse_ref[chk])
     np.testing.assert_allclose(lse[chk][fin], lse_ref[chk][fin], rtol=1e-3, atol=2e-3)
     assert np.all(np.isneginf(lse[chk][~fin]))
+    # the gather-free variant (Section 4.3, sparse loading) reads the same rows through the permutations:
+    # same arithmetic in the same order, so the same bits
+    gf = svg2.svg2_sparse_attn_gather_free(to_dev(Q[None], dtype), to_dev(K[None], dtype), to_dev(V[None], dtype),
+                                           to_dev(pq.offsets[None]), to_dev(pk.offsets[None]),
+                                           to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
+                                           to_dev(pk.perm[None]), want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(gf.O, res.O) and torch.equal(gf.lse, res.lse)
     return O, res
 
 
@@ -358,6 +366,26 @@ def test_forward_top_p_one_is_dense_attention(svg2, oracle):
     err = np.abs(to_np(res.O[0]) - O_ref)
     assert err.max() <= 2e-2 and err.mean() <= 1e-3
     assert float(res.aux.density[0]) == pytest.approx(1.0, rel=1e-6)
+
+
+@pytest.mark.parametrize("name,heads", [("tiny", [0]), ("small", [5, 20])])
+def test_forward_gather_free_equals_forward(svg2, name, heads):
+    w = wl.WORKLOADS[name]
+    Q, K, V, cq, ck = head_inputs(w, heads)
+    args = [to_dev(x, w.dtype) for x in (Q, K, V)]
+    a = svg2.svg2_forward(*args, to_dev(cq), to_dev(ck), w.top_p, w.iters, want_aux=True)
+    b = svg2.svg2_forward_gather_free(*args, to_dev(cq), to_dev(ck), w.top_p, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    for n in ("labels_q", "labels_k", "perm_q", "perm_k", "row_ptr", "density", "lse"):
+        assert torch.equal(getattr(a.aux, n), getattr(b.aux, n)), n
+    for h in range(len(heads)):                             # entries past a head's last row pointer are unused
+        nnz = int(a.aux.row_ptr[h, -1])
+        assert torch.equal(a.aux.col_idx[h, :nnz], b.aux.col_idx[h, :nnz])
+    assert torch.equal(a.O, b.O)
+    dt = 1 if w.dtype == "bf16" else 0
+    H, N, d = args[0].shape
+    assert (svg2.svg2_forward_workspace_size(dt, H, N, d, w.Cq, w.Ck) -
+            svg2.svg2_forward_workspace_size(dt, H, N, d, w.Cq, w.Ck, True)) >= 3 * args[0].numel() * args[0].element_size()
 
 
 def test_results_are_reproducible(svg2):
