@@ -12,6 +12,8 @@
  *   centroid scores + top-p    Section 4.2, Eq. 1 and Eq. 2, top-p rule
  *   block-sparse attention     Section 4.3 with the equivalence of Section 4.1
  *   density                    Section 5.1 "Metrics"
+ *   attention recall           Section 3.1 (attention mass the selected keys capture)
+ *   k-means++ seeding          Section 4.3 / 5.3 (the initialisation the paper starts from)
  *
  * Inputs are float arrays (bf16 workloads pass bf16-representable floats, so
  * reading them is exact); every sum is accumulated in double.  OpenMP is used
@@ -390,4 +392,106 @@ double svg2o_padding_waste(int rows, int cols, int bm, int bn)
     long long tiles_r = (rows + bm - 1) / bm, tiles_c = (cols + bn - 1) / bn;
     double padded = (double)(tiles_r * bm) * (double)(tiles_c * bn);
     return padded > 0.0 ? 1.0 - ((double)rows * (double)cols) / padded : 0.0;
+}
+
+/* ------------------------------------------------------------------------
+ * Attention recall, Section 3.1: for a query, the sum of the true attention
+ * scores (the softmax over ALL keys) of the keys that are computed.  Here the
+ * computed keys of query n are the keys whose cluster is selected for the
+ * cluster of n (Section 4.2).  Q, K [N,d] in ORIGINAL token order, labels_q,
+ * labels_k [N]; row_ptr / col_idx the CSR list of selected key clusters per
+ * query cluster.  rows != NULL: only those n_rows tokens are filled.
+ * ------------------------------------------------------------------------ */
+void svg2o_attention_recall(const float *Q, const float *K, int N, int d,
+                            const int32_t *labels_q, const int32_t *labels_k, int Cq, int Ck,
+                            const int32_t *row_ptr, const int32_t *col_idx, double scale,
+                            const int32_t *rows, int n_rows, double *recall)
+{
+    int total = rows ? n_rows : N;
+    /* selected[i * Ck + j] = 1 if key cluster j is selected for query cluster i */
+    unsigned char *selected = (unsigned char *)calloc((size_t)Cq * (size_t)Ck, 1);
+    for (int i = 0; i < Cq; ++i)
+        for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) selected[(size_t)i * Ck + col_idx[e]] = 1;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+#pragma omp for schedule(dynamic, 8)
+        for (int t = 0; t < total; ++t) {
+            int n = rows ? rows[t] : t;
+            const float *q = Q + (size_t)n * d;
+            double mx = -INFINITY;
+            for (int m = 0; m < N; ++m) {
+                const float *k = K + (size_t)m * d;
+                double a = 0.0;
+                for (int c = 0; c < d; ++c) a += (double)q[c] * (double)k[c];
+                s[m] = a * scale;
+                if (s[m] > mx) mx = s[m];
+            }
+            double den = 0.0, kept = 0.0;
+            const unsigned char *sel_row = selected + (size_t)labels_q[n] * Ck;
+            for (int m = 0; m < N; ++m) {
+                double p = exp(s[m] - mx);
+                den += p;
+                if (sel_row[labels_k[m]]) kept += p;
+            }
+            recall[n] = kept / den;
+        }
+        free(s);
+    }
+    free(selected);
+}
+
+/* ------------------------------------------------------------------------
+ * k-means++ seeding (the initialisation the paper's un-cached k-means starts
+ * from, Section 4.3; Arthur & Vassilvitskii's D^2 sampling).  The random
+ * numbers are inputs: u[C] uniform in [0,1).
+ *   centre 0      token floor(u[0] * N)
+ *   centre k >= 1 with D2[n] = min over the centres chosen so far of
+ *                 ||x_n - c||^2: the first token whose running sum of D2
+ *                 exceeds u[k] * sum(D2) (so a token is drawn with probability
+ *                 D2[n] / sum(D2)); if every D2 is zero, token floor(u[k] * N).
+ * picked[C] receives the token indices; the centres are those rows of X.
+ * ------------------------------------------------------------------------ */
+void svg2o_kmeans_pp(const float *X, int N, int d, int C, const double *u, int32_t *picked)
+{
+    double *d2 = (double *)malloc(sizeof(double) * (size_t)N);
+    for (int n = 0; n < N; ++n) d2[n] = INFINITY;
+    for (int k = 0; k < C; ++k) {
+        int pick;
+        if (k == 0) {
+            pick = (int)floor(u[0] * (double)N);
+        } else {
+            double total = 0.0;
+            for (int n = 0; n < N; ++n) total += d2[n];
+            if (total > 0.0) {
+                double target = u[k] * total, run = 0.0;
+                pick = -1;
+                for (int n = 0; n < N; ++n) {
+                    run += d2[n];
+                    if (run > target) { pick = n; break; }
+                }
+                if (pick < 0) {             /* rounding left the running sum at the target: last token with D2 > 0 */
+                    for (int n = N - 1; n >= 0; --n)
+                        if (d2[n] > 0.0) { pick = n; break; }
+                }
+            } else {
+                pick = (int)floor(u[k] * (double)N);
+            }
+        }
+        if (pick < 0) pick = 0;
+        if (pick > N - 1) pick = N - 1;
+        picked[k] = pick;
+        const float *c = X + (size_t)pick * d;
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < N; ++n) {
+            const float *x = X + (size_t)n * d;
+            double a = 0.0;
+            for (int j = 0; j < d; ++j) {
+                double t = (double)x[j] - (double)c[j];
+                a += t * t;
+            }
+            if (a < d2[n]) d2[n] = a;
+        }
+    }
+    free(d2);
 }

@@ -160,6 +160,31 @@ def sparse_attention(Qp, Kp, Vp, offsets_q, offsets_k, row_ptr, col_idx, perm_q=
     return O, lse
 
 
+def attention_recall(Q, K, labels_q, labels_k, Cq, Ck, row_ptr, col_idx, scale=None, rows=None):
+    """Section 3.1: per query token, the true attention mass of the keys its cluster's selection computes.
+    Q, K in original token order; with `rows` only those tokens are filled (others NaN)."""
+    Q, K = _f32(Q), _f32(K)
+    N, d = Q.shape
+    lq, lk, rp, ci = _i32(labels_q), _i32(labels_k), _i32(row_ptr), _i32(col_idx)
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = np.full(N, np.nan, dtype=np.float64)
+    rr = None if rows is None else _i32(rows)
+    _load().svg2o_attention_recall(_p(Q), _p(K), N, d, _p(lq), _p(lk), int(Cq), int(Ck), _p(rp), _p(ci),
+                                   ctypes.c_double(scale), _p(rr), 0 if rr is None else rr.shape[0], _p(out))
+    return out
+
+
+def kmeans_pp(X, C, u):
+    """k-means++ seeding with the uniform numbers u[C] given: (picked token indices [C], centres [C,d])."""
+    X = _f32(X)
+    N, d = X.shape
+    u = _f64(u)
+    assert u.shape == (C,)
+    picked = np.empty(C, dtype=np.int32)
+    _load().svg2o_kmeans_pp(_p(X), N, d, int(C), _p(u), _p(picked))
+    return picked, X[picked].copy()
+
+
 def padding_waste(rows, cols, bm, bn) -> float:
     return float(_load().svg2o_padding_waste(int(rows), int(cols), int(bm), int(bn)))
 

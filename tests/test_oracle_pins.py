@@ -402,3 +402,110 @@ def test_identification_cost_bound_from_the_paper():
         if l.strip() and l[0] != "#":
             N, Cq, Ck, bound = l.split()
             assert 2 * int(Cq) * int(Ck) / (4 * int(N) ** 2) < float(bound)
+
+
+# ------------------------------------------------------------------ attention recall (Section 3.1)
+
+def _recall_case(seed, N=96, d=16, Cq=5, Ck=7):
+    r = _rng(seed)
+    Q = r.standard_normal((N, d)).astype(np.float32)
+    K = r.standard_normal((N, d)).astype(np.float32)
+    lq = r.integers(0, Cq, N).astype(np.int32)
+    lk = r.integers(0, Ck, N).astype(np.int32)
+    sel = [np.sort(r.choice(Ck, size=int(r.integers(0, Ck + 1)), replace=False)) for _ in range(Cq)]
+    row_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sel])]).astype(np.int32)
+    col = np.concatenate(sel).astype(np.int32) if row_ptr[-1] else np.zeros(0, np.int32)
+    return Q, K, lq, lk, sel, row_ptr, col
+
+
+def test_recall_matches_library_softmax_brute_force(oracle):
+    Q, K, lq, lk, sel, row_ptr, col = _recall_case(50)
+    got = oracle.attention_recall(Q, K, lq, lk, 5, 7, row_ptr, col)
+    P = scipy.special.softmax((Q.astype(np.float64) @ K.astype(np.float64).T) / np.sqrt(Q.shape[1]), axis=1)
+    want = np.array([P[n, np.isin(lk, sel[lq[n]])].sum() for n in range(Q.shape[0])])
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+
+
+def test_recall_limits_and_complement(oracle):
+    Q, K, lq, lk, sel, row_ptr, col = _recall_case(51)
+    Cq, Ck = 5, 7
+    full_ptr = (np.arange(Cq + 1) * Ck).astype(np.int32)
+    full_col = np.tile(np.arange(Ck, dtype=np.int32), Cq)
+    np.testing.assert_allclose(oracle.attention_recall(Q, K, lq, lk, Cq, Ck, full_ptr, full_col), 1.0, rtol=1e-12)
+    none = oracle.attention_recall(Q, K, lq, lk, Cq, Ck, np.zeros(Cq + 1, np.int32), np.zeros(0, np.int32))
+    assert np.all(none == 0.0)
+    comp = [np.setdiff1d(np.arange(Ck), s) for s in sel]
+    cptr = np.concatenate([[0], np.cumsum([len(s) for s in comp])]).astype(np.int32)
+    ccol = np.concatenate(comp).astype(np.int32)
+    a = oracle.attention_recall(Q, K, lq, lk, Cq, Ck, row_ptr, col)
+    b = oracle.attention_recall(Q, K, lq, lk, Cq, Ck, cptr, ccol)
+    np.testing.assert_allclose(a + b, 1.0, rtol=1e-12)
+    assert np.all((a >= 0) & (a <= 1))
+
+
+def test_recall_is_ratio_of_softmax_denominators(oracle):
+    # sum over selected keys of softmax = exp(lse over the selected keys - lse over all keys): ties the recall to
+    # the (separately pinned) sparse and dense attention of the oracle
+    Q, K, lq, lk, sel, row_ptr, col = _recall_case(52)
+    V = _rng(53).standard_normal(Q.shape).astype(np.float32)
+    pq, pk = oracle.permute(lq, 5), oracle.permute(lk, 7)
+    _, lse_s = oracle.sparse_attention(Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets, row_ptr, col,
+                                       perm_q=pq.perm)
+    _, lse_d = oracle.dense_attention(Q, K, V)
+    got = oracle.attention_recall(Q, K, lq, lk, 5, 7, row_ptr, col)
+    np.testing.assert_allclose(got, np.exp(lse_s - lse_d), rtol=1e-10, atol=1e-300)
+
+
+def test_recall_of_the_oracle_policy_reaches_p(oracle):
+    # singleton clusters with centroids = tokens: P' is the exact attention (pinned above), so the top-p rule is
+    # the oracle policy of Section 3.1 and the recall of its selection is at least p for every query
+    r = _rng(54)
+    N, d, p = 40, 8, 0.8
+    Q = r.standard_normal((N, d)).astype(np.float32)
+    K = r.standard_normal((N, d)).astype(np.float32)
+    ident = np.arange(N, dtype=np.int32)
+    s = oracle.select_topp(Q.astype(np.float64), K.astype(np.float64), np.ones(N, np.int32), np.ones(N, np.int32), p)
+    rec = oracle.attention_recall(Q, K, ident, ident, N, N, s.row_ptr, s.col_idx)
+    assert np.all(rec >= p - 1e-12)
+    P = scipy.special.softmax((Q.astype(np.float64) @ K.astype(np.float64).T) / np.sqrt(d), axis=1)
+    for n in range(N):                                       # minimal: dropping the weakest kept key falls below p
+        kept = s.col_idx[s.row_ptr[n]: s.row_ptr[n + 1]]
+        assert rec[n] - P[n, kept].min() < p
+
+
+# ------------------------------------------------------------------ k-means++ seeding (Section 4.3)
+
+def test_kmeans_pp_draws_in_proportion_to_squared_distance(oracle):
+    # points on a line at 0, 1, 2, 3: after the first centre at 0 the squared distances are 0, 1, 4, 9, so the
+    # second centre is token 1, 2, 3 for u in [0, 1/14), [1/14, 5/14), [5/14, 1)
+    X = np.array([[0.0], [1.0], [2.0], [3.0]], dtype=np.float32)
+    grid = (np.arange(14000) + 0.5) / 14000.0
+    picks = np.array([oracle.kmeans_pp(X, 2, np.array([0.0, u]))[0][1] for u in grid])
+    assert set(picks) == {1, 2, 3}
+    np.testing.assert_array_equal(picks, np.where(grid < 1 / 14, 1, np.where(grid < 5 / 14, 2, 3)))
+    # first centre: token floor(u0 * N)
+    for u0, want in ((0.0, 0), (0.24, 0), (0.26, 1), (0.99, 3)):
+        assert oracle.kmeans_pp(X, 1, np.array([u0]))[0][0] == want
+
+
+def test_kmeans_pp_worked_example_three_centres(oracle):
+    # tokens (0,0), (3,0), (0,4), (3,4); u = (0.3 -> token 1), then D2 = 9, 0, 25, 16 (sum 50):
+    # u = 0.5 -> target 25 -> running sums 9, 9, 34 -> token 2; then D2 = 9, 0, 0, 9 (sum 18): u = 0.6 -> 10.8 -> token 3
+    X = np.array([[0, 0], [3, 0], [0, 4], [3, 4]], dtype=np.float32)
+    picked, centres = oracle.kmeans_pp(X, 3, np.array([0.3, 0.5, 0.6]))
+    np.testing.assert_array_equal(picked, [1, 2, 3])
+    np.testing.assert_array_equal(centres, X[[1, 2, 3]])
+
+
+def test_kmeans_pp_invariants(oracle):
+    r = _rng(60)
+    X = r.standard_normal((500, 12)).astype(np.float32)
+    u = r.random(40)
+    picked, centres = oracle.kmeans_pp(X, 40, u)
+    assert len(set(picked.tolist())) == 40                   # a chosen token has D2 = 0 and is never drawn again
+    np.testing.assert_array_equal(centres, X[picked])
+    pot = [np.min(((X[:, None, :] - X[picked[:k]][None]) ** 2).sum(-1), axis=1).sum() for k in range(1, 41)]
+    assert np.all(np.diff(pot) <= 1e-9)                      # the potential never grows as centres are added
+    # every D2 zero (all tokens identical): falls back to token floor(u * N)
+    same = np.ones((10, 3), dtype=np.float32)
+    np.testing.assert_array_equal(oracle.kmeans_pp(same, 3, np.array([0.05, 0.55, 0.95]))[0], [0, 5, 9])
