@@ -211,6 +211,41 @@ int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dt
                              void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * svg2_attention_recall -- Section 3.1: attention recall = the share of a
+ * query's true attention mass (softmax over ALL keys) that the computed keys
+ * capture.  For query n, with lse_selected[n] the log-sum-exp of its scores
+ * over the selected keys (svg2_sparse_attn's lse) and lse_all[n] the one over
+ * all keys (svg2_sparse_attn's lse in the dense special case),
+ * recall[n] = exp(lse_selected[n] - lse_all[n]) (0 when nothing is selected).
+ *   lse_selected, lse_all [H,N] fp32
+ *   recall      [H,N] fp32 out or NULL
+ *   recall_mean [H]   fp32 out          mean over the head's queries
+ * ------------------------------------------------------------------------- */
+size_t svg2_attention_recall_workspace_size(int H, int N);
+int svg2_attention_recall(const float *lse_selected, const float *lse_all, int H, int N,
+                          float *recall, float *recall_mean,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * svg2_kmeans_pp_init -- Sections 4.3 / 5.3: k-means++ seeding, the
+ * initialisation of a k-means that has no centroid cache to start from.
+ * Per head: centre 0 is token floor(u[0] N); centre k >= 1 is the first token
+ * whose running sum of D2 exceeds u[k] sum(D2), where D2 is the squared
+ * distance of a token to the nearest centre chosen so far (so a token is
+ * drawn with probability D2 / sum(D2)); if every D2 is zero, token
+ * floor(u[k] N).  The random numbers are the caller's.
+ *   X         [H,N,d] dtype
+ *   u         [H,C]   fp64              uniform numbers in [0,1)
+ *   centroids [H,C,d] fp32 out          the drawn tokens (input of svg2_kmeans)
+ *   picked    [H,C]   int32 out or NULL their token indices
+ * All arithmetic is fp64; C passes over X.
+ * ------------------------------------------------------------------------- */
+size_t svg2_kmeans_pp_init_workspace_size(int H, int N, int C);
+int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C,
+                        const double *u, float *centroids, int32_t *picked,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * Stage timing for benchmarks (HOST-side state, one per process).
  * svg2_profile_enable(1): every later svg2_forward call records HIP events
  * around its stages on the caller's stream (events are created on first use;

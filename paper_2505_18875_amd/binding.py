@@ -30,6 +30,8 @@ EXPORTS = (
     "svg2_sparse_attn_workspace_size", "svg2_sparse_attn", "svg2_sparse_attn_gather_free",
     "svg2_forward_workspace_size", "svg2_forward",
     "svg2_forward_gather_free_workspace_size", "svg2_forward_gather_free",
+    "svg2_attention_recall_workspace_size", "svg2_attention_recall",
+    "svg2_kmeans_pp_init_workspace_size", "svg2_kmeans_pp_init",
     "svg2_profile_enable", "svg2_profile_read",
 )
 STAGES = ("kmeans_q", "kmeans_k", "permute", "select", "attn_plan", "attn")
@@ -79,6 +81,10 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_forward.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, vp, sz, vp]
         lib.svg2_forward_gather_free_workspace_size.argtypes = [i, i, i, i, i, i]
         lib.svg2_forward_gather_free.argtypes = lib.svg2_forward.argtypes
+        lib.svg2_attention_recall_workspace_size.argtypes = [i, i]
+        lib.svg2_attention_recall.argtypes = [vp, vp, i, i, vp, vp, vp, sz, vp]
+        lib.svg2_kmeans_pp_init_workspace_size.argtypes = [i, i, i]
+        lib.svg2_kmeans_pp_init.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp, sz, vp]
         lib.svg2_profile_enable.argtypes = [i]
         lib.svg2_profile_read.argtypes = [vp, vp]
         _lib = lib
@@ -271,6 +277,37 @@ def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, o
                             _dev(ck_inout, torch.float32, "ck_inout"), _dev(O, Q.dtype, "O"), aux_p,
                             _dev(ws), ws.numel(), _stream()))
     return SimpleNamespace(O=O, aux=aux_t)
+
+
+def svg2_attention_recall(lse_selected, lse_all, *, want_rows=True, ws=None):
+    """Section 3.1.  lse of the selected keys and of all keys [H,N] fp32 -> recall per query (, mean per head)."""
+    lib = load_library()
+    H, N = lse_selected.shape
+    dev = lse_selected.device
+    rows = torch.empty((H, N), dtype=torch.float32, device=dev) if want_rows else None
+    mean = torch.empty((H,), dtype=torch.float32, device=dev)
+    need = lib.svg2_attention_recall_workspace_size(H, N)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_attention_recall(_dev(lse_selected, torch.float32, "lse_selected"),
+                                     _dev(lse_all, torch.float32, "lse_all"), H, N, _dev(rows), _dev(mean),
+                                     _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(recall=rows, mean=mean)
+
+
+def svg2_kmeans_pp_init(X, C, u, *, ws=None):
+    """Sections 4.3 / 5.3: k-means++ seeding with the caller's uniform numbers u [H,C] fp64 -> centroids, picked."""
+    lib = load_library()
+    H, N, d = X.shape
+    dev = X.device
+    if u.shape != (H, C):
+        raise ValueError("u must be [H,C]")
+    centroids = torch.empty((H, C, d), dtype=torch.float32, device=dev)
+    picked = torch.empty((H, C), dtype=torch.int32, device=dev)
+    need = lib.svg2_kmeans_pp_init_workspace_size(H, N, C)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_kmeans_pp_init(_dev(X, name="X"), _dtype_code(X), H, N, d, C, _dev(u, torch.float64, "u"),
+                                   _dev(centroids), _dev(picked), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(centroids=centroids, picked=picked)
 
 
 def svg2_profile_enable(enable: bool) -> None:

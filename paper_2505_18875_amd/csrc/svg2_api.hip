@@ -359,6 +359,40 @@ int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dt
                         stream, true);
 }
 
+size_t svg2_attention_recall_workspace_size(int H, int N)
+{
+    if (H < 1 || N < 1) return 256;
+    return recall_ws_bytes(H, N);
+}
+
+int svg2_attention_recall(const float *lse_selected, const float *lse_all, int H, int N, float *recall,
+                          float *recall_mean, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_REQUIRE(H >= 1 && H <= 65535 && N >= 1, SVG2_INVALID_ARG, "H = %d (1..65535) and N = %d must be positive", H, N);
+    SVG2_REQUIRE(lse_selected && lse_all && recall_mean, SVG2_INVALID_ARG,
+                 "lse_selected, lse_all and recall_mean must be non-null");
+    SVG2_TRY(check_ws(ws, ws_bytes, recall_ws_bytes(H, N)));
+    return recall_launch(lse_selected, lse_all, H, N, recall, recall_mean, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t svg2_kmeans_pp_init_workspace_size(int H, int N, int C)
+{
+    if (H < 1 || N < 1 || C < 1 || C > SVG2_MAX_CLUSTERS) return 256;
+    return kpp_ws_bytes(H, N, C);
+}
+
+int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C, const double *u, float *centroids,
+                        int32_t *picked, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_clusters("C", C, N));
+    SVG2_REQUIRE(X && u && centroids, SVG2_INVALID_ARG, "X, u and centroids must be non-null");
+    SVG2_TRY(check_ws(ws, ws_bytes, kpp_ws_bytes(H, N, C)));
+    return kpp_launch(X, dtype, H, N, d, C, u, centroids, picked, ws, static_cast<hipStream_t>(stream));
+}
+
 int svg2_profile_enable(int enable)
 {
     std::lock_guard<std::mutex> lk(g_prof.mu);

@@ -97,4 +97,12 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
                      const int32_t *row_ptr, const int32_t *perm_q, const int32_t *perm_k, float scale, void *O,
                      float *lse, void *ws, hipStream_t st);
 
+size_t recall_ws_bytes(int H, int N);
+int recall_launch(const float *lse_sel, const float *lse_all, int H, int N, float *recall, float *recall_mean,
+                  void *ws, hipStream_t st);
+
+size_t kpp_ws_bytes(int H, int N, int C);
+int kpp_launch(const void *X, int dtype, int H, int N, int d, int C, const double *u, float *centroids,
+               int32_t *picked, void *ws, hipStream_t st);
+
 }  // namespace svg2
