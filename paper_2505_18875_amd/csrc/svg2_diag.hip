@@ -16,7 +16,8 @@
 
 namespace svg2 {
 
-static constexpr int DG_BLOCK = 1024;       // tokens per workgroup (256 threads x 4)
+static constexpr int DG_BLOCK = 1024;       // tokens per workgroup in the recall kernel (256 threads x 4)
+static constexpr int KPP_BLOCK = 256;       // tokens per block sum in k-means++
 
 // ---------------------------------------------------------------- recall
 // grid (nblk, H), block 256
@@ -71,7 +72,7 @@ int recall_launch(const float *lse_sel, const float *lse_all, int H, int N, floa
 
 // ---------------------------------------------------------------- k-means++
 // One draw.  grid (H), block 256.  k = 0: token floor(u * N).  Otherwise the first token whose running
-// sum of D2 exceeds u * sum(D2): the workgroup first finds the 1024-token block in which the running sum
+// sum of D2 exceeds u * sum(D2): the workgroup first finds the block of KPP_BLOCK tokens in which the running sum
 // crosses the threshold (block sums come from the update kernel), then the token inside it.
 template <typename T>
 __global__ __launch_bounds__(256) void kpp_pick_kernel(const T *__restrict__ X, const double *__restrict__ u,
@@ -85,64 +86,65 @@ __global__ __launch_bounds__(256) void kpp_pick_kernel(const T *__restrict__ X, 
     const int h = blockIdx.x, tid = threadIdx.x;
     const double uk = u[(size_t)h * C + k];
     const double *dh = d2 + (size_t)h * N;
-    // total and the block in which the running sum crosses the threshold (thread 0, block sums staged in LDS)
-    __shared__ double s_total, s_run;
+    // The running sum is taken hierarchically (block sums, then groups of 4 tokens, then tokens), every level
+    // with a 256-wide inclusive scan in LDS; the first position whose inclusive sum exceeds the threshold wins.
+    __shared__ double s_base;
     __shared__ int s_blk;
-    if (tid == 0) { s_total = 0.0; s_pick = -1; s_blk = -1; s_run = 0.0; }
-    __syncthreads();
-    if (k > 0) {
-        for (int b0 = 0; b0 < nblk; b0 += 256) {
-            if (b0 + tid < nblk) s_scan[tid] = bsum[(size_t)h * nblk + b0 + tid];
+    auto scan256 = [&](double v) {              // inclusive scan over the workgroup (Hillis-Steele in LDS)
+        s_scan[tid] = v;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {
+            const double t = (tid >= o) ? s_scan[tid - o] : 0.0;
             __syncthreads();
-            if (tid == 0) {
-                double t = s_total;
-                for (int b = 0; b < min(256, nblk - b0); ++b) t += s_scan[b];
-                s_total = t;
-            }
+            s_scan[tid] += t;
             __syncthreads();
         }
-        const double target = uk * s_total;
-        if (s_total > 0.0) {
-            for (int b0 = 0; b0 < nblk && s_blk < 0; b0 += 256) {
-                if (b0 + tid < nblk) s_scan[tid] = bsum[(size_t)h * nblk + b0 + tid];
+        return s_scan[tid];
+    };
+    if (tid == 0) { s_pick = -1; s_blk = 0x7FFFFFFF; s_base = 0.0; }
+    __syncthreads();
+    if (k > 0) {
+        double total = 0.0;
+        for (int b0 = 0; b0 < nblk; b0 += 256) {
+            const double incl = scan256(b0 + tid < nblk ? bsum[(size_t)h * nblk + b0 + tid] : 0.0);
+            total += s_scan[255];
+            (void)incl;
+            __syncthreads();
+        }
+        const double target = uk * total;
+        if (total > 0.0) {
+            double base = 0.0;                  // running sum before the current chunk of 256 blocks
+            for (int b0 = 0; b0 < nblk; b0 += 256) {
+                const double v = b0 + tid < nblk ? bsum[(size_t)h * nblk + b0 + tid] : 0.0;
+                const double incl = base + scan256(v);
+                if (b0 + tid < nblk && incl > target) atomicMin(&s_blk, b0 + tid);
                 __syncthreads();
-                if (tid == 0) {
-                    double run = s_run;
-                    for (int b = 0; b < min(256, nblk - b0); ++b) {
-                        const double nx = run + s_scan[b];
-                        if (nx > target) { s_blk = b0 + b; break; }
-                        run = nx;
-                    }
-                    s_run = run;
+                if (s_blk != 0x7FFFFFFF) {
+                    if (tid == s_blk - b0) s_base = incl - v;      // running sum before the crossing block
+                    __syncthreads();
+                    break;
                 }
+                base += s_scan[255];
                 __syncthreads();
             }
-            // inside the block: every thread sums 4 consecutive tokens, thread 0 walks the 256 partial sums
-            // and then the 4 tokens of the group in which the running sum crosses
-            for (int blk = s_blk; blk >= 0 && blk < nblk; ++blk) {
-                const int n0 = blk * DG_BLOCK + 4 * tid;
-                double v[4];
-                for (int q = 0; q < 4; ++q) v[q] = (n0 + q < N) ? dh[n0 + q] : 0.0;
-                s_scan[tid] = ((v[0] + v[1]) + v[2]) + v[3];
+            // inside the block: one token per thread
+            for (int blk = s_blk; blk < nblk; ++blk) {
+                const int n = blk * KPP_BLOCK + tid;
+                const double v = (n < N) ? dh[n] : 0.0;
+                const double incl = s_base + scan256(v);
+                __shared__ int s_tok;
+                if (tid == 0) s_tok = 0x7FFFFFFF;
                 __syncthreads();
-                if (tid == 0) {
-                    double run = s_run;
-                    for (int g = 0; g < 256 && s_pick < 0; ++g) {
-                        if (run + s_scan[g] > target) {
-                            double r2 = run;
-                            for (int q = 0; q < 4; ++q) {
-                                const int n = blk * DG_BLOCK + 4 * g + q;
-                                if (n >= N) break;
-                                r2 += dh[n];
-                                if (r2 > target) { s_pick = n; break; }
-                            }
-                        }
-                        run += s_scan[g];
-                    }
-                    s_run = run;
+                if (n < N && incl > target) atomicMin(&s_tok, n);
+                __syncthreads();
+                if (s_tok != 0x7FFFFFFF) {
+                    if (tid == 0) s_pick = s_tok;
+                    __syncthreads();
+                    break;
                 }
                 __syncthreads();
-                if (s_pick >= 0) break;         // (rounding may push the crossing into the next block)
+                if (tid == 255) s_base = incl;  // rounding pushed the crossing into the next block
+                __syncthreads();
             }
             if (tid == 0 && s_pick < 0) {       // rounding left the running sum at the threshold
                 for (int n = N - 1; n >= 0; --n)
@@ -191,8 +193,8 @@ __device__ __forceinline__ void load_elems(const float *p, int per, double *out)
     }
 }
 
-// D2[n] = min(D2[n], ||x_n - c||^2) against the centre drawn last, and the sum of D2 per 1024-token block.
-// grid (nblk, H), block 256; 16 lanes share a token (d / 16 elements each), 16 tokens per pass.
+// D2[n] = min(D2[n], ||x_n - c||^2) against the centre drawn last, and the sum of D2 per KPP_BLOCK tokens.
+// grid (nblk, H), block 256; 16 lanes share a token (d / 16 elements each), 16 tokens per pass, 4 passes in flight.
 template <typename T>
 __global__ __launch_bounds__(256) void kpp_update_kernel(const T *__restrict__ X,
                                                          const int32_t *__restrict__ picked, int N, int d, int C,
@@ -208,22 +210,31 @@ __global__ __launch_bounds__(256) void kpp_update_kernel(const T *__restrict__ X
     double cv[8], xv[8];
     load_elems(c, per, cv);
     double acc = 0.0;
-    for (int r = 0; r < DG_BLOCK; r += 16) {
-        const int n = blockIdx.x * DG_BLOCK + r + sub;
-        double a = 0.0;
-        if (n < N) {
-            load_elems(Xh + (size_t)n * d + part * per, per, xv);
-            for (int j = 0; j < per; ++j) {
-                const double t = xv[j] - cv[j];
-                a += t * t;
+    for (int r = 0; r < KPP_BLOCK; r += 64) {
+        double a[4], old[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = blockIdx.x * KPP_BLOCK + r + 16 * q + sub;
+            a[q] = 0.0;
+            old[q] = INFINITY;
+            if (n < N) {
+                load_elems(Xh + (size_t)n * d + part * per, per, xv);
+                for (int j = 0; j < per; ++j) {
+                    const double t = xv[j] - cv[j];
+                    a[q] += t * t;
+                }
+                if (k > 0 && part == 0) old[q] = d2[(size_t)h * N + n];
             }
         }
-        for (int o = 1; o < 16; o <<= 1) a += __shfl_xor(a, o);
-        if (n < N && part == 0) {
-            const double old = (k == 0) ? INFINITY : d2[(size_t)h * N + n];
-            const double nv = a < old ? a : old;
-            d2[(size_t)h * N + n] = nv;
-            acc += nv;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            for (int o = 1; o < 16; o <<= 1) a[q] += __shfl_xor(a[q], o);
+            const int n = blockIdx.x * KPP_BLOCK + r + 16 * q + sub;
+            if (n < N && part == 0) {
+                const double nv = a[q] < old[q] ? a[q] : old[q];
+                d2[(size_t)h * N + n] = nv;
+                acc += nv;
+            }
         }
     }
     s_red[tid] = acc;
@@ -246,7 +257,7 @@ static KppWs kpp_carve(void *ws, int H, int N, int C)
     KppWs k;
     Carver c(ws);
     k.d2 = c.take<double>((size_t)H * N);
-    k.bsum = c.take<double>((size_t)H * cdiv(N, DG_BLOCK));
+    k.bsum = c.take<double>((size_t)H * cdiv(N, KPP_BLOCK));
     k.picked = c.take<int32_t>((size_t)H * C);
     k.total = c.used;
     return k;
@@ -260,7 +271,7 @@ static int kpp_run(const T *X, int H, int N, int d, int C, const double *u, floa
 {
     const KppWs w = kpp_carve(ws, H, N, C);
     int32_t *pk = picked ? picked : w.picked;
-    const int nblk = cdiv(N, DG_BLOCK);
+    const int nblk = cdiv(N, KPP_BLOCK);
     for (int k = 0; k < C; ++k) {
         hipLaunchKernelGGL(kpp_pick_kernel<T>, dim3(H), dim3(256), 0, st, X, u, w.d2, w.bsum, N, d, C, k, nblk, pk,
                            centroids);
