@@ -186,12 +186,28 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
     return w;
 }
 
+// v_max_f32 / v_max3_f32 as they are: fmaxf() makes the compiler first canonicalise each operand it cannot prove
+// quiet (one extra v_max_f32 x, x per operand); the scores here come out of the matrix cores and are never
+// signalling NaNs.  Not volatile: the scheduler may still place them.
+__device__ __forceinline__ float max2_raw(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float max3_raw(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // max / sum of a value with the one held by lane ^ 32 (v_permlane32_swap: no LDS round trip)
 __device__ __forceinline__ float max_xor32(float x)
 {
     const unsigned u = __float_as_uint(x);
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return max2_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float sum_xor32(float x)
 {
@@ -322,11 +338,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         const int kk = (KT) * ATT_BN + lane;                                               \
         int row_ = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
         if (perm_k) row_ = pkh[row_];           /* gather-free: sorted row -> token */     \
-        s_rows[((KT) & 1) * ATT_BN + lane] = row_;                                         \
+        s_rows[((KT) & 1) * ATT_BN + lane] = row_ * RB;     /* byte offset of the row */   \
     }
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
-        OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row] * (unsigned)RB;
+        OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
 #define ATT_FETCH(OFF, SRC, LOFF, DST)                                                     \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(SRC + (OFF[p_] + LOFF)), \
@@ -370,6 +386,13 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         const int cl = 2 * ((lane >> 4) & 1) + ((r16 & 3) >> 1);
 #pragma unroll
         for (int b = 0; b < DVB; ++b) voff[b] = kr0 * RB + ((((4 * b) ^ vz) + cl) * 16) + (r16 & 1) * 8;
+        // fold the address of the LDS buffer in once and make the sums opaque: otherwise the compiler re-adds the
+        // (link-time constant) base in front of every LDS read
+        const int lds_base = (int)(unsigned)(size_t)(const lds_u8 *)s_raw;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) { koff[s] += lds_base; asm volatile("" : "+v"(koff[s])); }
+#pragma unroll
+        for (int b = 0; b < DVB; ++b) { voff[b] += lds_base; asm volatile("" : "+v"(voff[b])); }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): queries and the first tiles have landed
     __syncthreads();
@@ -404,7 +427,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     constexpr int NPV = 2 * DVB;
     constexpr int NOPS = 48;                    // vector operations of one block's probabilities
     constexpr int OPS_B = ATT_OPS_B;            // of which phase B (of the block before) does the first OPS_B
-    const lds_u8 *lds = (const lds_u8 *)s_raw;
+    const lds_u8 *lds = (const lds_u8 *)0;      // koff / voff are complete LDS addresses
     f32x16 s0, s1;                              // scores of block 0 / block 1 of a tile
     unsigned pw0[8], pw1[8];                    // probabilities of block 0 / block 1, two bf16 per word
     bf16x8 ka[KS], va[NPV];                     // K operands of the next score block, V^T operands of this one
@@ -497,9 +520,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
             if (DO_MAX && idx < HB) {
 #pragma unroll
                 for (int c = (8 * idx) / HB; c < (8 * (idx + 1)) / HB; ++c) {
-                    if (c == 0) mx = fmaxf(fmaxf(Snext[0], Snext[1]), Snext[2]);
-                    else if (c < 7) mx = fmaxf(fmaxf(mx, Snext[2 * c + 1]), Snext[2 * c + 2]);
-                    else mx = fmaxf(mx, Snext[15]);
+                    // the first read of the new scores is an ordinary fmaxf, so that the compiler puts the wait
+                    // states between the matrix instructions and the vector read; the other reads come later
+                    if (c == 0) mx = max2_raw(fmaxf(Snext[0], Snext[1]), Snext[2]);
+                    else if (c < 7) mx = max3_raw(mx, Snext[2 * c + 1], Snext[2 * c + 2]);
+                    else mx = max2_raw(mx, Snext[15]);
                     ATT_PIN(mx)
                 }
                 if (idx == HB - 1) decide(mx);
