@@ -14,6 +14,7 @@
  *   density                    Section 5.1 "Metrics"
  *   attention recall           Section 3.1 (attention mass the selected keys capture)
  *   k-means++ seeding          Section 4.3 / 5.3 (the initialisation the paper starts from)
+ *   FP8 E4M3 quantisation      Table 1, "+ FP8" rows (per-head scaling: a reading, the paper gives no recipe)
  *
  * Inputs are float arrays (bf16 workloads pass bf16-representable floats, so
  * reading them is exact); every sum is accumulated in double.  OpenMP is used
@@ -494,4 +495,72 @@ void svg2o_kmeans_pp(const float *X, int N, int d, int C, const double *u, int32
         }
     }
     free(d2);
+}
+
+/* ------------------------------------------------------------------------
+ * FP8 storage for the attention operands (the "+ FP8" rows of Table 1; the
+ * paper does not say how the operands are quantised, so this is a reading):
+ * OCP 8-bit floating point E4M3 -- 1 sign bit, 4 exponent bits with bias 7,
+ * 3 mantissa bits, subnormals below 2^-6, no infinities, S.1111.111 is NaN,
+ * largest finite value 448 -- with one scale per head and tensor,
+ *     amax  = max |x| over the head's [N, d] block
+ *     inv   = 448 / amax          (single precision; 1 when amax is 0)
+ *     code  = E4M3(x * inv)       (single-precision product, round to
+ *                                  nearest, ties to even, clamped to +-448)
+ *     scale = amax / 448          (single precision; 1 when amax is 0)
+ * so that x ~ decode(code) * scale.  The products are taken in single
+ * precision on purpose: a rounding decision has to be taken in the same
+ * precision by whoever is compared with this.
+ * ------------------------------------------------------------------------ */
+
+/* nearest E4M3 value of y (ties to even mantissa), clamped to +-448 */
+double svg2o_round_e4m3(double y)
+{
+    if (y == 0.0 || isnan(y)) return y;
+    double a = fabs(y);
+    if (a >= 448.0) return copysign(448.0, y);
+    double q;                               /* spacing of the representable values around a */
+    if (a < ldexp(1.0, -6)) {
+        q = ldexp(1.0, -9);                 /* subnormal range */
+    } else {
+        int e;
+        (void)frexp(a, &e);                 /* a = m * 2^e, 0.5 <= m < 1: a in [2^(e-1), 2^e) */
+        q = ldexp(1.0, e - 1 - 3);          /* 3 mantissa bits */
+    }
+    double r = nearbyint(a / q) * q;        /* default rounding mode: ties to even */
+    if (r > 448.0) r = 448.0;
+    return copysign(r, y);
+}
+
+/* the 8-bit code of an E4M3 value v (as returned by svg2o_round_e4m3) */
+uint8_t svg2o_encode_e4m3(double v)
+{
+    uint8_t s = signbit(v) ? 0x80 : 0x00;
+    double a = fabs(v);
+    if (a == 0.0) return s;
+    if (a < ldexp(1.0, -6)) return (uint8_t)(s | (uint8_t)lrint(a * 512.0));      /* exponent field 0 */
+    int e;
+    double m = frexp(a, &e);                /* a = (2m) * 2^(e-1), 1 <= 2m < 2 */
+    int field = e - 1 + 7;
+    int mant = (int)lrint((2.0 * m - 1.0) * 8.0);
+    return (uint8_t)(s | (field << 3) | mant);
+}
+
+/* X [n] floats of one head and tensor -> codes [n], decoded [n] (= decode(code), unscaled), *scale */
+void svg2o_quantize_e4m3(const float *X, long n, uint8_t *codes, float *decoded, float *scale)
+{
+    float amax = 0.0f;
+    for (long i = 0; i < n; ++i) {
+        float a = fabsf(X[i]);
+        if (a > amax) amax = a;
+    }
+    volatile float inv = (amax > 0.0f) ? 448.0f / amax : 1.0f;
+    volatile float sc = (amax > 0.0f) ? amax / 448.0f : 1.0f;
+    for (long i = 0; i < n; ++i) {
+        volatile float y = X[i] * inv;      /* single-precision product, no contraction */
+        double r = svg2o_round_e4m3((double)y);
+        if (codes) codes[i] = svg2o_encode_e4m3(r);
+        if (decoded) decoded[i] = (float)r;
+    }
+    *scale = sc;
 }

@@ -185,6 +185,33 @@ def kmeans_pp(X, C, u):
     return picked, X[picked].copy()
 
 
+def round_e4m3(y):
+    """Nearest OCP E4M3 value (ties to even, clamped to +-448) of each element of y."""
+    lib = _load()
+    lib.svg2o_round_e4m3.restype = ctypes.c_double
+    y = np.asarray(y, dtype=np.float64)
+    return np.array([lib.svg2o_round_e4m3(ctypes.c_double(v)) for v in y.ravel()]).reshape(y.shape)
+
+
+def encode_e4m3(v):
+    """8-bit codes of E4M3 values."""
+    lib = _load()
+    lib.svg2o_encode_e4m3.restype = ctypes.c_uint8
+    v = np.asarray(v, dtype=np.float64)
+    return np.array([lib.svg2o_encode_e4m3(ctypes.c_double(x)) for x in v.ravel()], dtype=np.uint8).reshape(v.shape)
+
+
+def quantize_e4m3(X):
+    """One head of one tensor: (codes uint8, decoded float32 = decode(codes), scale float32) with
+    X ~ decoded * scale (per-head amax scaling, single-precision products)."""
+    X = _f32(X)
+    codes = np.empty(X.shape, dtype=np.uint8)
+    dec = np.empty(X.shape, dtype=np.float32)
+    sc = ctypes.c_float(0.0)
+    _load().svg2o_quantize_e4m3(_p(X), ctypes.c_long(X.size), _p(codes), _p(dec), ctypes.byref(sc))
+    return codes, dec, np.float32(sc.value)
+
+
 def padding_waste(rows, cols, bm, bn) -> float:
     return float(_load().svg2o_padding_waste(int(rows), int(cols), int(bm), int(bn)))
 

@@ -509,3 +509,91 @@ def test_kmeans_pp_invariants(oracle):
     # every D2 zero (all tokens identical): falls back to token floor(u * N)
     same = np.ones((10, 3), dtype=np.float32)
     np.testing.assert_array_equal(oracle.kmeans_pp(same, 3, np.array([0.05, 0.55, 0.95]))[0], [0, 5, 9])
+
+
+# ------------------------------------------------------------------ FP8 E4M3 storage of the attention operands
+
+def _e4m3_table():
+    """All finite E4M3 values from the format's definition: sign, 4 exponent bits (bias 7), 3 mantissa bits,
+    exponent field 0 subnormal, S.1111.111 not a number."""
+    vals = {}
+    for code in range(256):
+        s, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            continue
+        v = m * 2.0 ** -9 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
+        vals[code] = -v if s else v
+    return vals
+
+
+def test_e4m3_every_code_is_a_fixed_point_and_encodes_to_itself(oracle):
+    tab = _e4m3_table()
+    assert len(tab) == 254 and max(tab.values()) == 448.0 and tab[0x38] == 1.0 and tab[0x01] == 2.0 ** -9
+    codes = np.array(sorted(tab), dtype=np.uint8)
+    vals = np.array([tab[c] for c in codes])
+    np.testing.assert_array_equal(oracle.round_e4m3(vals), vals)
+    got = oracle.encode_e4m3(vals)
+    keep = vals != 0                                   # +0 and -0 compare equal as values
+    np.testing.assert_array_equal(got[keep], codes[keep])
+    assert oracle.encode_e4m3(np.array([0.0]))[0] == 0x00 and oracle.encode_e4m3(np.array([-0.0]))[0] == 0x80
+
+
+def test_e4m3_rounding_is_nearest_by_brute_force_with_ties_to_even(oracle):
+    tab = _e4m3_table()
+    pos = np.array(sorted(v for v in tab.values() if v >= 0 and not (v == 0 and np.signbit(v))))
+    pos = np.unique(pos)
+    r = _rng(40)
+    y = np.concatenate([r.uniform(-448, 448, 3000), r.standard_normal(3000) * 0.01, r.standard_normal(3000) * 3,
+                        10.0 ** r.uniform(-5, 2.6, 3000)])
+    got = oracle.round_e4m3(y)
+    # brute force: scan the whole table for the nearest value
+    d = np.abs(np.abs(y)[:, None] - pos[None, :])
+    near = pos[np.argmin(d, axis=1)]
+    not_tie = np.sort(d, axis=1)[:, 0] < np.sort(d, axis=1)[:, 1]
+    np.testing.assert_array_equal(np.abs(got[not_tie]), near[not_tie])
+    np.testing.assert_array_equal(np.sign(got[got != 0]), np.sign(y[got != 0]))
+    # exact midpoints go to the neighbour with the even mantissa (even code)
+    mids = (pos[:-1] + pos[1:]) / 2
+    gm = oracle.round_e4m3(mids)
+    code_of = {v: c for c, v in tab.items() if c < 0x80}
+    for lo, hi, g in zip(pos[:-1], pos[1:], gm):
+        want = lo if code_of[lo] % 2 == 0 else hi
+        assert g == want, (lo, hi, g)
+    np.testing.assert_array_equal(oracle.round_e4m3(-mids), -gm)
+    # clamping
+    np.testing.assert_array_equal(oracle.round_e4m3(np.array([448.1, 1e9, -500.0, 464.0])),
+                                  np.array([448.0, 448.0, -448.0, 448.0]))
+
+
+def test_e4m3_matches_the_library_conversion(oracle):
+    r = _rng(41)
+    y = np.concatenate([r.uniform(-440, 440, 4000), r.standard_normal(4000), r.standard_normal(2000) * 0.004,
+                        np.array([0.0, 2.0 ** -10, 2.0 ** -10 * 1.0001, 3 * 2.0 ** -10, 447.9, -448.0])]).astype(np.float32)
+    lib = torch.from_numpy(y).to(torch.float8_e4m3fn)
+    np.testing.assert_array_equal(oracle.round_e4m3(y.astype(np.float64)), lib.to(torch.float64).numpy())
+    nz = lib.to(torch.float64).numpy() != 0
+    np.testing.assert_array_equal(oracle.encode_e4m3(oracle.round_e4m3(y.astype(np.float64)))[nz],
+                                  lib.view(torch.uint8).numpy()[nz])
+
+
+def test_quantize_e4m3_scale_and_error_bound(oracle):
+    r = _rng(42)
+    X = (r.standard_normal((300, 16)) * np.exp(r.standard_normal((300, 1)))).astype(np.float32)
+    codes, dec, sc = oracle.quantize_e4m3(X)
+    amax = np.abs(X).max()
+    assert sc == np.float32(amax) / np.float32(448.0)
+    assert np.abs(dec).max() == 448.0                  # the largest element lands on the largest code
+    tab = _e4m3_table()
+    np.testing.assert_array_equal(dec, np.array([tab[c] for c in codes.ravel()], dtype=np.float32).reshape(dec.shape))
+    # library route: same single-precision scaling, library rounding
+    inv = np.float32(448.0) / np.float32(amax)
+    lib = torch.from_numpy((X * inv).astype(np.float32)).clamp(-448, 448).to(torch.float8_e4m3fn)
+    np.testing.assert_array_equal(dec, lib.to(torch.float32).numpy())
+    # relative error of a normal value is at most half a unit in the last of 3 mantissa bits (plus the fp32 product)
+    y = X.astype(np.float64) * float(inv)
+    normal = np.abs(y) >= 2.0 ** -6
+    assert np.all(np.abs(dec[normal] - y[normal]) <= np.abs(y[normal]) * (2.0 ** -4 + 1e-6))
+    assert np.all(np.abs(dec[~normal] - y[~normal]) <= 2.0 ** -10 + 1e-9)
+    # all-zero input: scale 1, codes 0
+    c0, d0, s0 = oracle.quantize_e4m3(np.zeros((4, 8), dtype=np.float32))
+    assert s0 == 1.0 and not c0.any() and not d0.any()
