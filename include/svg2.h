@@ -211,6 +211,53 @@ int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dt
                              void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * FP8 attention -- the "+ FP8" rows of Table 1.  The paper names the precision
+ * but not the recipe; this library's reading: Q, K and V are stored as OCP
+ * E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, largest value
+ * 448, no infinities) with ONE scale per head and tensor; scores, softmax and
+ * accumulators are fp32; the probabilities enter the second matrix product as
+ * E4M3 as well.  k-means, permutation and selection are unchanged (they read
+ * the bf16 tensors).  Head dimension 128 and SVG2_BF16 outputs only
+ * (SVG2_UNSUPPORTED otherwise).
+ *
+ * svg2_quantize_fp8: per head h, amax = max |X[h]|, X8 = E4M3(X * (448 / amax))
+ * (single-precision product, round to nearest even), scale[h] = amax / 448, so
+ * X ~ decode(X8) * scale[h]; an all-zero head gets scale 1.
+ *   X [H,N,d] dtype; X8 [H,N,d] bytes out; scale [H] fp32 out
+ *
+ * svg2_sparse_attn_fp8: svg2_sparse_attn on such operands.
+ *   Q8, K8, V8 [H,N,d] bytes; scale_q, scale_k, scale_v [H] fp32
+ *   perm_k NULL: the operands are the PERMUTED copies (perm_q optional, as in
+ *   svg2_sparse_attn); perm_k given: they are in token order and rows are
+ *   fetched through perm_q / perm_k (as in svg2_sparse_attn_gather_free).
+ *   O [H,N,d] bf16 out, lse [H,N] fp32 out or NULL (of the scores the kernel
+ *   actually used, i.e. of the quantised operands).
+ *   Workspace: svg2_sparse_attn_workspace_size(SVG2_BF16, ...).
+ *
+ * svg2_forward_fp8: svg2_forward_gather_free with the attention step on E4M3
+ * copies of Q, K, V (made in the workspace, in token order).  Arguments and
+ * results as svg2_forward; dtype must be SVG2_BF16.
+ * ------------------------------------------------------------------------- */
+size_t svg2_quantize_fp8_workspace_size(int H);
+int svg2_quantize_fp8(const void *X, int dtype, int H, int N, int d,
+                      void *X8, float *scale,
+                      void *ws, size_t ws_bytes, void *stream);
+int svg2_sparse_attn_fp8(const void *Q8, const void *K8, const void *V8,
+                         const float *scale_q, const float *scale_k, const float *scale_v,
+                         int H, int N, int d, int Cq, int Ck,
+                         const int32_t *offsets_q, const int32_t *offsets_k,
+                         const int32_t *row_ptr, const int32_t *col_idx,
+                         const int32_t *perm_q, const int32_t *perm_k,
+                         float scale, void *O, float *lse,
+                         void *ws, size_t ws_bytes, void *stream);
+size_t svg2_forward_fp8_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck);
+int svg2_forward_fp8(const void *Q, const void *K, const void *V, int dtype,
+                     int H, int N, int d, int Cq, int Ck, float top_p, int iters,
+                     float *cq_inout, float *ck_inout, void *O,
+                     const svg2_forward_aux *aux,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
  * svg2_attention_recall -- Section 3.1: attention recall = the share of a
  * query's true attention mass (softmax over ALL keys) that the computed keys
  * capture.  For query n, with lse_selected[n] the log-sum-exp of its scores

@@ -30,6 +30,8 @@ EXPORTS = (
     "svg2_sparse_attn_workspace_size", "svg2_sparse_attn", "svg2_sparse_attn_gather_free",
     "svg2_forward_workspace_size", "svg2_forward",
     "svg2_forward_gather_free_workspace_size", "svg2_forward_gather_free",
+    "svg2_quantize_fp8_workspace_size", "svg2_quantize_fp8", "svg2_sparse_attn_fp8",
+    "svg2_forward_fp8_workspace_size", "svg2_forward_fp8",
     "svg2_attention_recall_workspace_size", "svg2_attention_recall",
     "svg2_kmeans_pp_init_workspace_size", "svg2_kmeans_pp_init",
     "svg2_profile_enable", "svg2_profile_read",
@@ -81,6 +83,12 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_forward.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, i, vp, vp, vp, vp, vp, sz, vp]
         lib.svg2_forward_gather_free_workspace_size.argtypes = [i, i, i, i, i, i]
         lib.svg2_forward_gather_free.argtypes = lib.svg2_forward.argtypes
+        lib.svg2_quantize_fp8_workspace_size.argtypes = [i]
+        lib.svg2_quantize_fp8.argtypes = [vp, i, i, i, i, vp, vp, vp, sz, vp]
+        lib.svg2_sparse_attn_fp8.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp, vp, vp, vp, vp, vp, f, vp, vp,
+                                             vp, sz, vp]
+        lib.svg2_forward_fp8_workspace_size.argtypes = [i, i, i, i, i, i]
+        lib.svg2_forward_fp8.argtypes = lib.svg2_forward.argtypes
         lib.svg2_attention_recall_workspace_size.argtypes = [i, i]
         lib.svg2_attention_recall.argtypes = [vp, vp, i, i, vp, vp, vp, sz, vp]
         lib.svg2_kmeans_pp_init_workspace_size.argtypes = [i, i, i]
@@ -235,10 +243,53 @@ def svg2_sparse_attn_gather_free(Q, K, V, offsets_q, offsets_k, row_ptr, col_idx
     return SimpleNamespace(O=O, lse=lse)
 
 
-def svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck, gather_free=False) -> int:
+def svg2_quantize_fp8(X, *, ws=None):
+    """Table 1 (+ FP8): X [H,N,d] -> (X8 [H,N,d] uint8 E4M3 codes, scale [H] fp32), X ~ decode(X8) * scale[h]."""
     lib = load_library()
-    fn = lib.svg2_forward_gather_free_workspace_size if gather_free else lib.svg2_forward_workspace_size
+    H, N, d = X.shape
+    dev = X.device
+    X8 = torch.empty((H, N, d), dtype=torch.uint8, device=dev)
+    scale = torch.empty((H,), dtype=torch.float32, device=dev)
+    ws = _workspace(lib.svg2_quantize_fp8_workspace_size(H), dev) if ws is None else ws
+    _check(lib.svg2_quantize_fp8(_dev(X, name="X"), _dtype_code(X), H, N, d, _dev(X8), _dev(scale), _dev(ws),
+                                 ws.numel(), _stream()))
+    return X8, scale
+
+
+def svg2_sparse_attn_fp8(Q8, K8, V8, scale_q, scale_k, scale_v, offsets_q, offsets_k, row_ptr, col_idx,
+                         perm_q=None, perm_k=None, *, scale=0.0, want_lse=False, out=None, ws=None):
+    """Section 4.3 on E4M3 operands.  perm_k None: permuted copies; perm_k given: token order (gather-free)."""
+    lib = load_library()
+    H, N, d = Q8.shape
+    Cq, Ck = offsets_q.shape[1] - 1, offsets_k.shape[1] - 1
+    dev = Q8.device
+    if col_idx.numel() < H * Cq * Ck:
+        raise ValueError("col_idx must have capacity H*Cq*Ck")
+    O = torch.empty((H, N, d), dtype=torch.bfloat16, device=dev) if out is None else out
+    lse = torch.empty((H, N), dtype=torch.float32, device=dev) if want_lse else None
+    need = lib.svg2_sparse_attn_workspace_size(SVG2_BF16, H, N, d, Cq, Ck)
+    ws = _workspace(need, dev) if ws is None else ws
+    _check(lib.svg2_sparse_attn_fp8(
+        _dev(Q8, torch.uint8, "Q8"), _dev(K8, torch.uint8, "K8"), _dev(V8, torch.uint8, "V8"),
+        _dev(scale_q, torch.float32, "scale_q"), _dev(scale_k, torch.float32, "scale_k"),
+        _dev(scale_v, torch.float32, "scale_v"), H, N, d, Cq, Ck,
+        _dev(offsets_q, torch.int32, "offsets_q"), _dev(offsets_k, torch.int32, "offsets_k"),
+        _dev(row_ptr, torch.int32, "row_ptr"), _dev(col_idx, torch.int32, "col_idx"),
+        _dev(perm_q, torch.int32, "perm_q"), _dev(perm_k, torch.int32, "perm_k"), float(scale),
+        _dev(O, torch.bfloat16, "O"), _dev(lse), _dev(ws), ws.numel(), _stream()))
+    return SimpleNamespace(O=O, lse=lse)
+
+
+def svg2_forward_workspace_size(dtype_code, H, N, d, Cq, Ck, gather_free=False, fp8=False) -> int:
+    lib = load_library()
+    fn = (lib.svg2_forward_fp8_workspace_size if fp8 else
+          lib.svg2_forward_gather_free_workspace_size if gather_free else lib.svg2_forward_workspace_size)
     return fn(dtype_code, H, N, d, Cq, Ck)
+
+
+def svg2_forward_fp8(Q, K, V, cq_inout, ck_inout, top_p, iters, **kw):
+    """svg2_forward with the attention step on E4M3 copies of Q, K, V (Table 1, + FP8)."""
+    return svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, fp8=True, **kw)
 
 
 def svg2_forward_gather_free(Q, K, V, cq_inout, ck_inout, top_p, iters, **kw):
@@ -247,7 +298,7 @@ def svg2_forward_gather_free(Q, K, V, cq_inout, ck_inout, top_p, iters, **kw):
 
 
 def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, out=None, ws=None,
-                 gather_free=False):
+                 gather_free=False, fp8=False):
     """Section 4, the whole layer.  cq_inout / ck_inout [H,C,d] fp32 are updated in place (centroid cache)."""
     lib = load_library()
     H, N, d = Q.shape
@@ -269,9 +320,9 @@ def svg2_forward(Q, K, V, cq_inout, ck_inout, top_p, iters, *, want_aux=False, o
             lse=torch.empty((H, N), dtype=torch.float32, device=dev))
         aux_s = _ForwardAux(**{n: getattr(aux_t, n).data_ptr() for n, _ in _ForwardAux._fields_})
         aux_p = ctypes.cast(ctypes.pointer(aux_s), ctypes.c_void_p)
-    need = svg2_forward_workspace_size(dt, H, N, d, Cq, Ck, gather_free)
+    need = svg2_forward_workspace_size(dt, H, N, d, Cq, Ck, gather_free, fp8)
     ws = _workspace(need, dev) if ws is None else ws
-    entry = lib.svg2_forward_gather_free if gather_free else lib.svg2_forward
+    entry = lib.svg2_forward_fp8 if fp8 else lib.svg2_forward_gather_free if gather_free else lib.svg2_forward
     _check(entry(_dev(Q, name="Q"), _dev(K, Q.dtype, "K"), _dev(V, Q.dtype, "V"), dt, H, N, d, Cq, Ck,
                             float(top_p), int(iters), _dev(cq_inout, torch.float32, "cq_inout"),
                             _dev(ck_inout, torch.float32, "ck_inout"), _dev(O, Q.dtype, "O"), aux_p,

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsvg2_hip.so")
-SOURCES = ["svg2_api.hip", "svg2_permute.hip", "svg2_select.hip", "svg2_kmeans.hip", "svg2_attn.hip", "svg2_diag.hip"]
+SOURCES = ["svg2_api.hip", "svg2_permute.hip", "svg2_select.hip", "svg2_kmeans.hip", "svg2_attn.hip", "svg2_fp8.hip",
+           "svg2_diag.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-result", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

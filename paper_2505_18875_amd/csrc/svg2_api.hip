@@ -34,6 +34,14 @@ static int check_common(int dtype, int H, int N, int d)
     return SVG2_OK;
 }
 
+// the E4M3 attention kernel exists for bf16 inputs / outputs and 128-byte rows only
+static int check_fp8(int dtype, int d)
+{
+    SVG2_REQUIRE(dtype == SVG2_BF16, SVG2_UNSUPPORTED, "the FP8 path takes SVG2_BF16 tensors, not dtype %d", dtype);
+    SVG2_REQUIRE(d == 128, SVG2_UNSUPPORTED, "the FP8 path needs head dimension 128, not %d", d);
+    return SVG2_OK;
+}
+
 static int check_clusters(const char *name, int C, int N)
 {
     SVG2_REQUIRE(C >= 1 && C <= SVG2_MAX_CLUSTERS && C <= N, SVG2_INVALID_ARG,
@@ -60,13 +68,20 @@ struct ForwardLayout {
     int32_t *labels_q, *labels_k, *counts_q, *counts_k, *offsets_q, *offsets_k, *perm_q, *perm_k, *row_ptr, *col_idx;
     float *density;
     void *Qp, *Kp, *Vp;
+    void *Q8, *K8, *V8;                  // E4M3 copies in token order (fp8 mode only)
+    float *sq, *sk, *sv;                 // their per-head scales
     void *stage_ws;
     size_t stage_bytes, total;
 };
 
-// gather_free: no permuted copies of Q, K, V (the attention kernel reads rows through the permutations)
-static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, int Cq, int Ck, bool gather_free)
+// mode of svg2_forward: physical permutation, gather-free (no permuted copies of Q, K, V: the attention
+// kernel reads rows through the permutations), or gather-free on E4M3 copies of Q, K, V
+enum ForwardMode { FWD_PERMUTE = 0, FWD_GATHER_FREE = 1, FWD_FP8 = 2 };
+
+static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, int Cq, int Ck, int mode)
 {
+    const bool gather_free = mode != FWD_PERMUTE;
+    const bool fp8 = mode == FWD_FP8;
     ForwardLayout L;
     Carver c(ws);
     const size_t es = dtype == SVG2_BF16 ? 2 : 4;
@@ -84,6 +99,12 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     L.Qp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
     L.Kp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
     L.Vp = c.take<char>(gather_free ? 0 : (size_t)H * N * d * es);
+    L.Q8 = c.take<char>(fp8 ? (size_t)H * N * d : 0);
+    L.K8 = c.take<char>(fp8 ? (size_t)H * N * d : 0);
+    L.V8 = c.take<char>(fp8 ? (size_t)H * N * d : 0);
+    L.sq = c.take<float>(fp8 ? (size_t)H : 0);
+    L.sk = c.take<float>(fp8 ? (size_t)H : 0);
+    L.sv = c.take<float>(fp8 ? (size_t)H : 0);
     // the stages run one after another on one stream and share one scratch area
     size_t s = kmeans_ws_bytes(dtype, H, N, d, Cq);
     size_t t = kmeans_ws_bytes(dtype, H, N, d, Ck);
@@ -93,6 +114,8 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     t = select_ws_bytes(H, Cq, Ck);
     if (t > s) s = t;
     t = attn_ws_bytes(dtype, H, N, d, Cq, Ck);
+    if (t > s) s = t;
+    t = fp8 ? fp8_quant_ws_bytes(H) : 0;
     if (t > s) s = t;
     L.stage_bytes = s;
     L.stage_ws = c.take<char>(s);
@@ -259,7 +282,7 @@ size_t svg2_forward_workspace_size(int dtype, int H, int N, int d, int Cq, int C
     if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("Cq", Cq, N) != SVG2_OK ||
         check_clusters("Ck", Ck, N) != SVG2_OK)
         return 256;
-    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, false).total;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, FWD_PERMUTE).total;
 }
 
 size_t svg2_forward_gather_free_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
@@ -267,17 +290,19 @@ size_t svg2_forward_gather_free_workspace_size(int dtype, int H, int N, int d, i
     if (check_common(dtype, H, N, d) != SVG2_OK || check_clusters("Cq", Cq, N) != SVG2_OK ||
         check_clusters("Ck", Ck, N) != SVG2_OK)
         return 256;
-    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, true).total;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, FWD_GATHER_FREE).total;
 }
 
 }  // extern "C"
 
 static int forward_impl(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
                         float top_p, int iters, float *cq_inout, float *ck_inout, void *O,
-                        const svg2_forward_aux *aux, void *ws, size_t ws_bytes, void *stream, bool gather_free)
+                        const svg2_forward_aux *aux, void *ws, size_t ws_bytes, void *stream, int mode)
 {
     clear_error();
+    const bool gather_free = mode != FWD_PERMUTE;
     SVG2_TRY(check_common(dtype, H, N, d));
+    if (mode == FWD_FP8) SVG2_TRY(check_fp8(dtype, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));
     SVG2_TRY(check_clusters("Ck", Ck, N));
     SVG2_REQUIRE(iters >= 1, SVG2_INVALID_ARG, "iters = %d must be at least 1", iters);
@@ -286,7 +311,7 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
                  "Q, K, V, O, cq_inout and ck_inout must be non-null");
     SVG2_REQUIRE(O != Q && O != K && O != V, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_REQUIRE(ws != nullptr, SVG2_INVALID_ARG, "workspace pointer is null");
-    ForwardLayout L = forward_layout(ws, dtype, H, N, d, Cq, Ck, gather_free);
+    ForwardLayout L = forward_layout(ws, dtype, H, N, d, Cq, Ck, mode);
     SVG2_TRY(check_ws(ws, ws_bytes, L.total));
     float *lse = nullptr;
     if (aux) {
@@ -323,6 +348,11 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
     void *dst_k[2] = {L.Kp, L.Vp};
     SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, gather_free ? 0 : 2, src_k, dst_k,
                             dtype, d, L.stage_ws, st));
+    if (mode == FWD_FP8) {              // E4M3 copies in token order, one scale per head and tensor
+        SVG2_TRY(fp8_quant_launch(Q, dtype, H, N, d, L.Q8, L.sq, L.stage_ws, st));
+        SVG2_TRY(fp8_quant_launch(K, dtype, H, N, d, L.K8, L.sk, L.stage_ws, st));
+        SVG2_TRY(fp8_quant_launch(V, dtype, H, N, d, L.V8, L.sv, L.stage_ws, st));
+    }
     profile_mark(pb, 3, st);
     // Section 4.2: which (query cluster, key cluster) pairs to compute
     SVG2_TRY(select_launch(cq_inout, ck_inout, L.counts_q, L.counts_k, H, Cq, Ck, d, top_p, L.row_ptr, L.col_idx,
@@ -331,7 +361,10 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
     // Section 4.3: attention over the selected pairs, result back in token order
     SVG2_TRY(attn_plan_launch(dtype, H, N, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx, L.stage_ws, st));
     profile_mark(pb, 5, st);
-    if (gather_free)
+    if (mode == FWD_FP8)
+        SVG2_TRY(attn_fp8_main_launch(L.Q8, L.K8, L.V8, L.sq, L.sk, L.sv, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, L.perm_k,
+                                      0.f, O, lse, L.stage_ws, st));
+    else if (gather_free)
         SVG2_TRY(attn_main_launch(Q, K, V, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, L.perm_k, 0.f, O, lse,
                                   L.stage_ws, st));
     else
@@ -348,7 +381,7 @@ int svg2_forward(const void *Q, const void *K, const void *V, int dtype, int H, 
                  void *ws, size_t ws_bytes, void *stream)
 {
     return forward_impl(Q, K, V, dtype, H, N, d, Cq, Ck, top_p, iters, cq_inout, ck_inout, O, aux, ws, ws_bytes,
-                        stream, false);
+                        stream, FWD_PERMUTE);
 }
 
 int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq,
@@ -356,7 +389,63 @@ int svg2_forward_gather_free(const void *Q, const void *K, const void *V, int dt
                              const svg2_forward_aux *aux, void *ws, size_t ws_bytes, void *stream)
 {
     return forward_impl(Q, K, V, dtype, H, N, d, Cq, Ck, top_p, iters, cq_inout, ck_inout, O, aux, ws, ws_bytes,
-                        stream, true);
+                        stream, FWD_GATHER_FREE);
+}
+
+size_t svg2_forward_fp8_workspace_size(int dtype, int H, int N, int d, int Cq, int Ck)
+{
+    if (check_common(dtype, H, N, d) != SVG2_OK || check_fp8(dtype, d) != SVG2_OK ||
+        check_clusters("Cq", Cq, N) != SVG2_OK || check_clusters("Ck", Ck, N) != SVG2_OK)
+        return 256;
+    return forward_layout(nullptr, dtype, H, N, d, Cq, Ck, FWD_FP8).total;
+}
+
+int svg2_forward_fp8(const void *Q, const void *K, const void *V, int dtype, int H, int N, int d, int Cq, int Ck,
+                     float top_p, int iters, float *cq_inout, float *ck_inout, void *O, const svg2_forward_aux *aux,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    return forward_impl(Q, K, V, dtype, H, N, d, Cq, Ck, top_p, iters, cq_inout, ck_inout, O, aux, ws, ws_bytes,
+                        stream, FWD_FP8);
+}
+
+size_t svg2_quantize_fp8_workspace_size(int H)
+{
+    if (H < 1) return 256;
+    return fp8_quant_ws_bytes(H);
+}
+
+int svg2_quantize_fp8(const void *X, int dtype, int H, int N, int d, void *X8, float *scale, void *ws, size_t ws_bytes,
+                      void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_REQUIRE(X && X8 && scale, SVG2_INVALID_ARG, "X, X8 and scale must be non-null");
+    SVG2_REQUIRE(X != X8, SVG2_INVALID_ARG, "X8 must not alias X");
+    SVG2_TRY(check_ws(ws, ws_bytes, fp8_quant_ws_bytes(H)));
+    return fp8_quant_launch(X, dtype, H, N, d, X8, scale, ws, static_cast<hipStream_t>(stream));
+}
+
+int svg2_sparse_attn_fp8(const void *Q8, const void *K8, const void *V8, const float *scale_q, const float *scale_k,
+                         const float *scale_v, int H, int N, int d, int Cq, int Ck, const int32_t *offsets_q,
+                         const int32_t *offsets_k, const int32_t *row_ptr, const int32_t *col_idx,
+                         const int32_t *perm_q, const int32_t *perm_k, float scale, void *O, float *lse, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    clear_error();
+    SVG2_TRY(check_common(SVG2_BF16, H, N, d));
+    SVG2_TRY(check_fp8(SVG2_BF16, d));
+    SVG2_TRY(check_clusters("Cq", Cq, N));
+    SVG2_TRY(check_clusters("Ck", Ck, N));
+    SVG2_REQUIRE(Q8 && K8 && V8 && scale_q && scale_k && scale_v && O && offsets_q && offsets_k && row_ptr && col_idx,
+                 SVG2_INVALID_ARG,
+                 "Q8, K8, V8, the three scales, O, offsets_q, offsets_k, row_ptr and col_idx must be non-null");
+    SVG2_REQUIRE(!perm_k || perm_q, SVG2_INVALID_ARG, "perm_k (operands in token order) needs perm_q");
+    SVG2_REQUIRE(O != Q8 && O != K8 && O != V8, SVG2_INVALID_ARG, "O must not alias an input");
+    SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(SVG2_BF16, H, N, d, Cq, Ck)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SVG2_TRY(attn_plan_launch(SVG2_BF16, H, N, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, ws, st));
+    return attn_fp8_main_launch(Q8, K8, V8, scale_q, scale_k, scale_v, H, N, d, Cq, Ck, row_ptr, perm_q, perm_k, scale,
+                                O, lse, ws, st);
 }
 
 size_t svg2_attention_recall_workspace_size(int H, int N)

@@ -97,6 +97,15 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
                      const int32_t *row_ptr, const int32_t *perm_q, const int32_t *perm_k, float scale, void *O,
                      float *lse, void *ws, hipStream_t st);
 
+// E4M3 storage (svg2_fp8.hip)
+size_t fp8_quant_ws_bytes(int H);
+int fp8_quant_launch(const void *X, int dtype, int H, int N, int d, void *X8, float *scale, void *ws, hipStream_t st);
+// the plan is the bf16 one (attn_plan_launch with SVG2_BF16); perm_k as in attn_main_launch
+int attn_fp8_main_launch(const void *Q8, const void *K8, const void *V8, const float *scale_q, const float *scale_k,
+                         const float *scale_v, int H, int N, int d, int Cq, int Ck, const int32_t *row_ptr,
+                         const int32_t *perm_q, const int32_t *perm_k, float scale, void *O, float *lse, void *ws,
+                         hipStream_t st);
+
 size_t recall_ws_bytes(int H, int N);
 int recall_launch(const float *lse_sel, const float *lse_all, int H, int N, float *recall, float *recall_mean,
                   void *ws, hipStream_t st);

@@ -1,0 +1,224 @@
+"""GPU parity of the FP8 (E4M3) attention path (Table 1, "+ FP8" rows) against the CPU oracle.
+
+The quantiser is compared bit for bit (codes and scales).  The attention kernel is compared with
+the oracle's block-sparse attention evaluated on the SAME quantised operands (decoded codes, scales
+folded in), so what is left is the kernel's own arithmetic: fp32 scores and softmax, probabilities
+rounded to E4M3 (3 mantissa bits: relative rounding error within 2^-4, about 0.026 rms), fp32
+accumulation, bf16 output.  Tolerances (derived from that):
+  * O:   relative rms error over the checked rows <= 0.036 (the rms of a uniform rounding error of
+         2^-4 half-width; an output is a weighted mean of values with independent errors of that
+         size on the weights), and no element further off than 0.03 max|V| of its head;
+  * lse: the row sum is the sum of the rounded probabilities, so |lse - ref| <= ln(1 + 2^-4) = 0.0606
+         in the worst case, and far less on average (<= 0.01) unless a row's probabilities are all
+         nearly equal (then they all round the same way).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_18875_amd import workloads as wl
+from _util import head_inputs, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+O_REL_RMS, O_MAX_FRAC, LSE_MAX, LSE_MEAN = 0.036, 0.03, 0.0606 + 2e-3, 0.01
+
+
+@pytest.fixture(scope="module")
+def svg2():
+    import paper_2505_18875_amd as pkg
+    pkg.load_library()
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _quantise_all(svg2, *tensors):
+    out = [svg2.svg2_quantize_fp8(t) for t in tensors]
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("name,heads", [("small", [0, 13]), ("tiny", [0])])
+def test_quantize_fp8_matches_oracle_bit_for_bit(svg2, oracle, name, heads):
+    w = wl.WORKLOADS[name]
+    Q, K, V, _, _ = head_inputs(w, heads)
+    for X in (Q, K, V):
+        X8, scale = svg2.svg2_quantize_fp8(to_dev(X, w.dtype))
+        torch.cuda.synchronize()
+        for i in range(len(heads)):
+            codes, _, sc = oracle.quantize_e4m3(X[i])
+            assert float(scale[i]) == float(sc)
+            np.testing.assert_array_equal(X8[i].cpu().numpy(), codes)
+
+
+def test_quantize_fp8_ties_signs_zero_heads(svg2, oracle):
+    # head 0: amax = 448, so the scaling is exact and every value is its own pre-rounding value: all E4M3 values,
+    # all midpoints between neighbours (ties go to the even code), values next to the midpoints, both signs
+    tab = np.unique(np.abs(oracle.round_e4m3(np.linspace(-448, 448, 20001))))
+    mids = (tab[:-1] + tab[1:]) / 2
+    vals = np.concatenate([tab, mids, np.nextafter(mids.astype(np.float32), np.float32(0)),
+                           np.nextafter(mids.astype(np.float32), np.float32(1e9)), [448.0]])
+    vals = np.concatenate([vals, -vals]).astype(np.float32)
+    n = 64 * ((vals.size + 63) // 64)
+    X = np.zeros((3, n // 64, 64), dtype=np.float32)
+    X[0].reshape(-1)[: vals.size] = vals
+    X[2] = np.random.default_rng(0).standard_normal((n // 64, 64)) * 1e-30      # tiny values: scale far from 1
+    X8, scale = svg2.svg2_quantize_fp8(to_dev(X))                 # head 1 stays all zero: scale 1, codes 0
+    torch.cuda.synchronize()
+    for h in range(3):
+        codes, _, sc = oracle.quantize_e4m3(X[h])
+        assert float(scale[h]) == float(sc)
+        np.testing.assert_array_equal(X8[h].cpu().numpy(), codes)
+    assert float(scale[0]) == 1.0 and float(scale[1]) == 1.0 and not X8[1].any()
+
+
+def _oracle_on_quantised(oracle, Q, K, V, a, i, d, rows):
+    """Oracle attention of head i on the decoded E4M3 operands; returns (O, lse) indexed by token."""
+    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
+    pq, pk = to_np(a.perm_q[i]), to_np(a.perm_k[i])
+    rp, ci = to_np(a.row_ptr[i]), to_np(a.col_idx[i])
+    sc = (1.0 / np.sqrt(d)) * float(dq[2]) * float(dk[2])
+    O, lse = oracle.sparse_attention(dq[1][pq], dk[1][pk], dv[1][pk], to_np(a.offsets_q[i]), to_np(a.offsets_k[i]),
+                                     rp, ci[: rp[-1]], perm_q=pq, scale=sc, rows=rows)
+    return O * float(dv[2]), lse, pq
+
+
+def _check_against(O, lse, O_ref, lse_ref, tok, vmax, lse_mean=LSE_MEAN):
+    err = O[tok] - O_ref[tok]
+    rel = np.sqrt((err ** 2).mean() / max((O_ref[tok] ** 2).mean(), 1e-30))
+    assert rel <= O_REL_RMS, rel
+    assert np.abs(err).max() <= O_MAX_FRAC * vmax, (np.abs(err).max(), vmax)
+    fin = np.isfinite(lse_ref[tok])
+    dl = np.abs(lse[tok][fin] - lse_ref[tok][fin])
+    assert dl.max() <= LSE_MAX and dl.mean() <= lse_mean, (dl.max(), dl.mean())
+    assert np.all(np.isneginf(lse[tok][~fin]))
+
+
+@pytest.mark.parametrize("heads,top_p", [([2, 19], 0.9), ([7], 0.5)])
+def test_sparse_attn_fp8_matches_oracle_on_the_quantised_operands(svg2, oracle, heads, top_p):
+    w = wl.replace(wl.WORKLOADS["small"], top_p=top_p)
+    Q, K, V, cq, ck = head_inputs(w, heads)
+    Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
+    a = svg2.svg2_forward(Qd, Kd, Vd, to_dev(cq), to_dev(ck), w.top_p, w.iters, want_aux=True).aux
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, Qd, Kd, Vd)
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, a.offsets_q, a.offsets_k, a.row_ptr, a.col_idx,
+                                    a.perm_q, a.perm_k, want_lse=True)
+    torch.cuda.synchronize()
+    for i, h in enumerate(heads):
+        rows = np.sort(np.random.default_rng(h).choice(w.N, 512, replace=False)).astype(np.int32)
+        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, Q[i], K[i], V[i], a, i, w.d, rows)
+        _check_against(to_np(res.O[i]).astype(np.float64), to_np(res.lse[i]).astype(np.float64), O_ref, lse_ref,
+                       pq[rows], np.abs(V[i]).max())
+    # the operands as permuted copies (perm_k = None): same rows in the same order, same bits
+    def gather(X8, perm):
+        return torch.gather(X8, 1, perm.long()[:, :, None].expand(-1, -1, X8.shape[2])).contiguous()
+    cp = svg2.svg2_sparse_attn_fp8(gather(Q8, a.perm_q), gather(K8, a.perm_k), gather(V8, a.perm_k), sq, sk, sv,
+                                   a.offsets_q, a.offsets_k, a.row_ptr, a.col_idx, a.perm_q, None, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(cp.O, res.O) and torch.equal(cp.lse, res.lse)
+
+
+def test_sparse_attn_fp8_ragged_and_empty_clusters(svg2, oracle):
+    r = np.random.default_rng(77)
+    N, d, Cq, Ck = 1500, 128, 9, 40
+    Q, K, V = (wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32)) for _ in range(3))
+    V[:, 5] *= 30.0                                             # one wide channel sets the head's V scale
+    V = wl.round_to_bf16(V)
+    lq = r.integers(0, Cq, size=N).astype(np.int32)
+    lq[lq == 4] = 5                                             # empty query cluster
+    lq[:700] = 0                                                # one query cluster spanning several row tiles
+    lk = r.integers(0, Ck, size=N).astype(np.int32)
+    lk[lk == 7] = 8                                             # empty key cluster
+    sel = [np.sort(r.choice(Ck, size=int(r.integers(1, Ck)), replace=False)) for _ in range(Cq)]
+    sel[1] = np.array([7], dtype=np.int64)                      # only an empty key cluster: rows get O = 0
+    sel[2] = np.zeros(0, dtype=np.int64)                        # nothing selected at all
+    sel[3] = np.arange(Ck)                                      # everything
+    sel[6] = np.array([int(np.argmin(np.bincount(lk, minlength=Ck) + 1000 * (np.bincount(lk, minlength=Ck) == 0)))])
+    pq, pk = oracle.permute(lq, Cq), oracle.permute(lk, Ck)
+    row_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sel])]).astype(np.int32)
+    col = np.zeros(Cq * Ck, dtype=np.int32)
+    cat = np.concatenate(sel).astype(np.int32)
+    col[: cat.size] = cat
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, to_dev(Q[None], "bf16"), to_dev(K[None], "bf16"),
+                                                 to_dev(V[None], "bf16"))
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, to_dev(pq.offsets[None]), to_dev(pk.offsets[None]),
+                                    to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
+                                    to_dev(pk.perm[None]), want_lse=True)
+    torch.cuda.synchronize()
+    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
+    O_ref, lse_ref = oracle.sparse_attention(dq[1][pq.perm], dk[1][pk.perm], dv[1][pk.perm], pq.offsets, pk.offsets,
+                                             row_ptr, cat, perm_q=pq.perm,
+                                             scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
+    O_ref *= float(dv[2])
+    O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    _check_against(O, lse, O_ref, lse_ref, np.arange(N), np.abs(V).max())
+    for i in (1, 2):
+        rows = np.nonzero(lq == i)[0]
+        assert rows.size and np.all(O[rows] == 0.0) and np.all(np.isneginf(lse[rows]))
+
+
+def test_sparse_attn_fp8_dense_special_case_flat_and_peaked_rows(svg2, oracle):
+    # one cluster on each side = dense attention.  Half of the queries are tiny (flat softmax over 3000 keys:
+    # every probability is about 2^-11.5 of the sum and must not be flushed to zero), half are large (peaked).
+    r = np.random.default_rng(6)
+    N, d = 3000, 128
+    Q, K, V = (r.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    Q[: N // 2] *= 0.01
+    Q[N // 2:] *= 3.0
+    Q, K, V = wl.round_to_bf16(Q), wl.round_to_bf16(K), wl.round_to_bf16(V)
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, to_dev(Q[None], "bf16"), to_dev(K[None], "bf16"),
+                                                 to_dev(V[None], "bf16"))
+    one = to_dev(np.array([[0, N]], dtype=np.int32))
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, one, one, to_dev(np.array([[0, 1]], dtype=np.int32)),
+                                    to_dev(np.zeros((1, 1), dtype=np.int32)), None, None, want_lse=True)
+    torch.cuda.synchronize()
+    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
+    O_ref, lse_ref = oracle.dense_attention(dq[1], dk[1], dv[1], scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
+    O_ref = O_ref * float(dv[2])
+    O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    # flat rows: all probabilities of a row are nearly the same number and round the same way, so the error of
+    # the row sum does not average out -- only the worst-case bound holds for lse (the output is a ratio of two
+    # sums with that common factor and keeps its accuracy)
+    _check_against(O, lse, O_ref, lse_ref, np.arange(N // 2), np.abs(V).max(), lse_mean=LSE_MAX)
+    _check_against(O, lse, O_ref, lse_ref, np.arange(N // 2, N), np.abs(V).max())
+
+
+def test_forward_fp8_same_selection_as_forward_and_close_output(svg2, oracle):
+    w = wl.WORKLOADS["small"]
+    heads = [3, 11]
+    Q, K, V, cq, ck = head_inputs(w, heads)
+    Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
+    cq1, ck1, cq2, ck2 = to_dev(cq), to_dev(ck), to_dev(cq), to_dev(ck)
+    ref = svg2.svg2_forward(Qd, Kd, Vd, cq1, ck1, w.top_p, w.iters, want_aux=True)
+    res = svg2.svg2_forward_fp8(Qd, Kd, Vd, cq2, ck2, w.top_p, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    # everything before the attention step reads the bf16 tensors: identical
+    for n in ("labels_q", "labels_k", "counts_q", "counts_k", "offsets_q", "offsets_k", "perm_q", "perm_k", "row_ptr",
+              "density"):
+        assert torch.equal(getattr(res.aux, n), getattr(ref.aux, n)), n
+    assert torch.equal(cq1, cq2) and torch.equal(ck1, ck2)
+    # the attention step equals the stand-alone entry points on the same operands
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, Qd, Kd, Vd)
+    a = res.aux
+    alone = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, a.offsets_q, a.offsets_k, a.row_ptr, a.col_idx,
+                                      a.perm_q, a.perm_k, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(alone.O, res.O) and torch.equal(alone.lse, a.lse)
+    # against the oracle on the quantised operands
+    for i, h in enumerate(heads):
+        rows = np.sort(np.random.default_rng(h).choice(w.N, 256, replace=False)).astype(np.int32)
+        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, Q[i], K[i], V[i], a, i, w.d, rows)
+        _check_against(to_np(res.O[i]).astype(np.float64), to_np(a.lse[i]).astype(np.float64), O_ref, lse_ref,
+                       pq[rows], np.abs(V[i]).max())
+
+
+def test_fp8_entry_points_reject_what_they_do_not_support(svg2):
+    from paper_2505_18875_amd.binding import Svg2Error
+    x64 = torch.zeros((1, 256, 64), dtype=torch.bfloat16, device="cuda")
+    c64 = torch.zeros((1, 4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(Svg2Error, match="head dimension 128"):
+        svg2.svg2_forward_fp8(x64, x64, x64, c64, c64.clone(), 0.9, 1)
+    x32 = torch.zeros((1, 256, 128), dtype=torch.float32, device="cuda")
+    c128 = torch.zeros((1, 4, 128), dtype=torch.float32, device="cuda")
+    with pytest.raises(Svg2Error, match="SVG2_BF16"):
+        svg2.svg2_forward_fp8(x32, x32, x32, c128, c128.clone(), 0.9, 1)
