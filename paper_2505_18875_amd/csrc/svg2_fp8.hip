@@ -8,19 +8,28 @@
 //   fp8_amax_kernel / fp8_quant_kernel   per-head amax (partial maxima, no atomics), then x * (448 / amax)
 //                      rounded to nearest even by v_cvt_pk_fp8_f32.
 //   attn_fp8_kernel    the block-sparse attention of Section 4.3 on E4M3
-//                      operands: v_mfma_f32_32x32x16_fp8_fp8, same work items,
-//                      key tiles and transposed-score layout as the bf16 kernel,
-//                      rows half as long.  What differs:
+//                      operands: v_mfma_f32_32x32x64_f8f6f4 (the gfx950 instruction that
+//                      runs E4M3 at twice the bf16 rate; the older 32x32x16 fp8 form runs
+//                      at the bf16 rate), same work items, key tiles and transposed-score
+//                      layout as the bf16 kernel, rows half as long.  What differs:
+//                      * one instruction contracts 64 values: two per 32-key score block,
+//                        and the second product is taken once per 64-key tile;
 //                      * a probability is exp2(s - m) with the reference level m
 //                        kept 2^6 BELOW the running maximum (re-levelled only when a
-//                        score would exceed m by more than 8), so probabilities
+//                        score would exceed m by more than 2^8), so probabilities
 //                        span (2^-9 .. 2^8] and the small ones of a flat row still
 //                        land on normal E4M3 numbers;
-//                      * the row sum is one more matrix instruction per 16 keys
-//                        (a V^T row of ones), so it is the sum of the ROUNDED
-//                        probabilities, the same numbers that multiply V;
+//                      * the row sum is one more matrix instruction per tile (a V^T row
+//                        of ones), so it is the sum of the ROUNDED probabilities, the
+//                        same numbers that multiply V;
 //                      * V^T comes out of LDS with the 8-bit transposing read
 //                        (ds_read_b64_tr_b8).
+//
+// Two things the compiler does not take care of with these instructions (both seen as rare,
+// run-to-run varying errors before they were handled): it places 18 wait states between a
+// 32x32x64 f8f6f4 instruction and a vector instruction that touches its last result registers,
+// the hardware needs 20 (measured); and it does not look into asm statements when it places
+// the wait state a transcendental result needs before its first use.
 #include <type_traits>
 
 #include "svg2_attn_shared.h"
@@ -28,6 +37,7 @@
 namespace svg2 {
 
 typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 static constexpr float E4M3_MAX = 448.0f;
 
@@ -177,8 +187,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     int group, bf16_t *__restrict__ O, float *__restrict__ lse)
 {
     static_assert(D == 128, "row = 128 bytes: the swizzles below are written for that");
-    constexpr int KS = D / 16;                 // k-steps of QK^T
-    constexpr int KP = KS / 2;                 // 16-byte LDS reads per K row and half (two k-steps each)
+    constexpr int KU = D / 64;                 // matrix instructions per score block (64 values of d each)
     constexpr int DVB = D / 32;                // 32-row blocks of O^T
     constexpr int RB = D;                      // bytes per K / V row
     constexpr int CPR = RB / 16;               // 16-byte chunks per row
@@ -225,30 +234,30 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     const char *Kb = reinterpret_cast<const char *>(K + (size_t)h * N * D);
     const char *Vb = reinterpret_cast<const char *>(V + (size_t)h * N * D);
 
-    // ---- queries as the B operand of S^T = K Q^T.  A k-step covers 16 values of d, 8 per lane half;
-    // lane half hf takes bytes 32 u + 16 hf .. + 16 of its row for the k-steps 2 u and 2 u + 1 (one
-    // 16-byte access), and the K operand below is cut the same way.
-    long qreg[KS];
+    // ---- queries as the B operand of S^T = K Q^T.  One matrix instruction contracts 64 values of d,
+    // 32 per lane half: half hf takes bytes 64 u + 32 hf .. + 32 of its row for instruction u, and
+    // the K operand below is cut the same way (the instruction pairs byte j of the A lane with
+    // byte j of the B lane of the same half, so any common order of the contraction index works).
+    i32x8 qreg[KU];
     {
         int r = row0 + min(nrows - 1, wave * 32 + col);
         if (perm_k) r = perm_q[(size_t)h * N + r];
-        const uint4 *src = reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + 16 * half);
+        const uint4 *src = reinterpret_cast<const uint4 *>(Qh + (size_t)r * D + 32 * half);
 #pragma unroll
-        for (int u = 0; u < KP; ++u) {
-            const uint4 w = src[2 * u];
-            __builtin_memcpy(&qreg[2 * u], &w, 16);
+        for (int u = 0; u < KU; ++u) {
+            const uint4 w0 = src[4 * u], w1 = src[4 * u + 1];
+            __builtin_memcpy(&qreg[u], &w0, 16);
+            __builtin_memcpy(reinterpret_cast<char *>(&qreg[u]) + 16, &w1, 16);
         }
     }
     const bool wave_active = wave * 32 < nrows;
 
-    f32x16 oacc[DVB], lacc;
-    float m_run = -INFINITY;
+    f32x16 oacc[DVB];
+    float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
     for (int b = 0; b < DVB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) lacc[i] = 0.f;
 
     // ---- loader: as in the bf16 kernel (rows looked up by one wavefront, global -> LDS directly)
     const int32_t *pkh = perm_k ? perm_k + (size_t)h * N : nullptr;
@@ -292,15 +301,16 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     if (ntile > 2) { ATT_ROWS(2) }
     // off_nx stays live: the rows of tile 1, whose V is requested at the top of tile 0
 
-    // per-lane LDS read addresses (buffer 0): K operand pair u, V^T operand of column block b
-    int koff[KP], voff[DVB];
+    // per-lane LDS read addresses (buffer 0): the two 16-byte halves of K operand u, V^T operand of column block b
+    int koff[2 * KU], voff[DVB];
     {
         const int kz = (col >> 1) & 7;
 #pragma unroll
-        for (int u = 0; u < KP; ++u) koff[u] = col * RB + (((2 * u + half) ^ kz) * 16);
-        // V^T: lane r16 of a 16-lane block passes key i = r16 / 2 of the k-step's 8 keys of this lane half
-        // (k index i <-> key 8 (i / 4) + 4 half + i % 4, the order the probabilities come in) and the 8 output
-        // columns 32 b + 16 g16 + 8 (r16 % 2) ..; the read hands lane l the column 32 b + l % 32.
+        for (int c = 0; c < 2 * KU; ++c) koff[c] = col * RB + (((4 * (c >> 1) + 2 * half + (c & 1)) ^ kz) * 16);
+        // V^T: lane r16 of a 16-lane block passes key i = r16 / 2 of the 8 keys this lane half has in a group of
+        // 16 keys (byte j = 8 t + i of the operand <-> key 16 t + 8 (i / 4) + 4 half + i % 4 of the tile, the
+        // order the probabilities come in) and the 8 output columns 32 b + 16 g16 + 8 (r16 % 2) ..; the read
+        // hands lane l the column 32 b + l % 32.
         const int r16 = lane & 15, g16 = (lane >> 4) & 1, i = r16 >> 1;
         const int krow = 8 * (i >> 2) + 4 * half + (i & 3);
         const int vz = 2 * (((krow >> 1) & 1) + 2 * ((krow >> 3) & 1));
@@ -308,34 +318,41 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         for (int b = 0; b < DVB; ++b) voff[b] = krow * RB + ((((2 * b) ^ vz) + g16) * 16) + (r16 & 1) * 8;
         const int lds_base = (int)(unsigned)(size_t)(const lds_u8 *)s_raw;
 #pragma unroll
-        for (int u = 0; u < KP; ++u) { koff[u] += lds_base; asm volatile("" : "+v"(koff[u])); }
+        for (int c = 0; c < 2 * KU; ++c) { koff[c] += lds_base; asm volatile("" : "+v"(koff[c])); }
 #pragma unroll
         for (int b = 0; b < DVB; ++b) { voff[b] += lds_base; asm volatile("" : "+v"(voff[b])); }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
     __syncthreads();
 
-    // ---- schedule: the two-phase software pipeline of the bf16 kernel.
-    //   phase A(j):  S_{j+1} = K_{j+1} Q^T   ||  P_j = exp2(S_j - m) -> E4M3, LDS reads of V_j^T
-    //   phase B(j):  O^T += V_j^T P_j^T, l += 1^T P_j^T   ||  maximum of S_{j+1}, decision about m,
-    //                                                         LDS reads of K_{j+2}
-    // Accumulator i of a score block is key 8 (i/4) + 4 half + i%4; word e of pw holds accumulators
-    // 4 e .. 4 e + 3, and the words 2 t, 2 t + 1 are the B operand of k-step t (16 keys).
+    // ---- schedule.  Scores and probabilities are handled in blocks of 32 keys (two per tile), the second
+    // product once per 64-key tile (its contraction index is the whole tile).  Per tile t, with s0 = scores of
+    // its block 0 already there and the reference level m decided for them:
+    //   A:  s1 = K_{t,1} Q^T          (2 matrix instructions)  ||  pw0 = exp2(s0 - m), LDS reads of V_t^T and K_{t+1,0}
+    //   B:  maximum of s1, decision about m.  If m moved (rare): pw0 is recomputed under the new m and
+    //       the accumulators are rescaled, so that both halves of the tile share one level.
+    //   C:  s0 = K_{t+1,0} Q^T        (2)                      ||  pw1 = exp2(s1 - m), LDS reads of V_t^T and K_{t+1,1}
+    //   D:  O^T += V_t^T P^T, l += 1^T P^T   (4 + 1)           ||  maximum of the new s0, decision about m; the
+    //       accumulators are rescaled after the five instructions if m moved.
+    // Accumulator i of a score block is key 8 (i/4) + 4 half + i%4 of the block; word e of pw holds accumulators
+    // 4 e .. 4 e + 3; the B operand of the second product is pw0[0..3], pw1[0..3].
 #define ATT_FENCE __builtin_amdgcn_sched_barrier(0);
 #define ATT_PIN(X) asm volatile("" : "+v"(X));
-    constexpr int NPV = 2 * DVB;                // matrix instructions of O^T per block (the row sum adds 2)
     constexpr int NOPS = 40;                    // vector operations of one block's probabilities
     const lds_u8 *lds = (const lds_u8 *)0;
-    const long ones = 0x3838383838383838L;      // eight E4M3 1.0
+    i32x8 ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = 0x38383838;          // E4M3 1.0
     f32x16 s0, s1;
-    unsigned pw0[4], pw1[4];
-    long ka[KS], va[NPV];
-    float alpha = 1.f, t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+    i32x8 pw;                                   // probabilities of the tile: words 0..3 block 0, 4..7 block 1
+    i32x8 ka[KU], va[DVB];                      // K operands of the next score block, V^T operands of this tile
+    float m_acc = 0.f, t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+    int tw = 0;
+    f32x16 lt = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // row sums of the tile just accumulated
     bool any_upd = false;
 
-    // operation `op` (0..39) of the probabilities of one block: 10 per word (4 fma, 4 exp2, 2 conversions)
-    auto exp_op = [&](const f32x16 &S, unsigned *pw, int op) {
-        const int e = op / 10, k = op % 10;
+    auto exp_op = [&](const f32x16 &S, auto w0_tag, int op) {
+        const int e = op / 10, k = op % 10, w = decltype(w0_tag)::value + e;
         if (k == 0) { t0 = fmaf(S[4 * e], scale_log2, -m_run); ATT_PIN(t0) }
         else if (k == 1) { t1 = fmaf(S[4 * e + 1], scale_log2, -m_run); ATT_PIN(t1) }
         else if (k == 2) { t2 = fmaf(S[4 * e + 2], scale_log2, -m_run); ATT_PIN(t2) }
@@ -344,8 +361,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         else if (k == 5) { t1 = __builtin_amdgcn_exp2f(t1); ATT_PIN(t1) }
         else if (k == 6) { t2 = __builtin_amdgcn_exp2f(t2); ATT_PIN(t2) }
         else if (k == 7) { t3 = __builtin_amdgcn_exp2f(t3); ATT_PIN(t3) }
-        else if (k == 8) { pw[e] = (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, 0, false); ATT_PIN(pw[e]) }
-        else { pw[e] = (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, (int)pw[e], true); ATT_PIN(pw[e]) }
+        else if (k == 8) { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, 0, false); ATT_PIN(tw) }
+        else { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, tw, true); ATT_PIN(tw) pw[w] = tw; }
     };
     auto mask_block = [&](f32x16 &S, int base, int rem) {
 #pragma unroll
@@ -356,97 +373,132 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         const float mx_s = max_xor32(mx) * scale_log2;
         const bool upd = mx_s > m_run + F8_HEADROOM;
         any_upd = __any(upd);
-        const float m_new = upd ? mx_s - F8_LEVEL : m_run;
-        alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        m_run = upd ? mx_s - F8_LEVEL : m_run;
         ATT_PIN(m_run)
-        ATT_PIN(alpha)
     };
-    auto load_k = [&](auto kbyte_tag, int u) {
+    // The accumulators are expressed under the level m_acc; bring them to m_run.  Called once per tile, right
+    // before the tile is accumulated (both decisions since the last tile are folded into one factor).  The
+    // multiplications are written as in-place instructions: left to the compiler, the rescaled accumulators land
+    // in other registers and the common path (nothing to rescale) pays for it with register copies.
+    auto rescale_if_needed = [&]() {
+        if (__any(m_acc != m_run)) {
+            float alpha = __builtin_amdgcn_exp2f(m_acc - m_run);
+            // the exponential comes out of the transcendental unit; the compiler does not look into the asm
+            // statements below when it places the wait state such a result needs before its first use
+            asm volatile("s_nop 3" : "+v"(alpha));
+            m_acc = m_run;
+            l_run *= alpha;
+#pragma unroll
+            for (int b = 0; b < DVB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(oacc[b][i]) : "v"(alpha));
+        }
+    };
+    // 16-byte half c (0 .. 2 KU - 1) of the K operands of a score block whose first row is at KBYTE
+    auto load_k = [&](auto kbyte_tag, int c) {
         constexpr int KBYTE = decltype(kbyte_tag)::value;
-        const u32x4 w = lds_read_b128((lds + koff[u]) + KBYTE);
-        __builtin_memcpy(&ka[2 * u], &w, 16);
+        const u32x4 w = lds_read_b128((lds + koff[c]) + KBYTE);
+        __builtin_memcpy(reinterpret_cast<char *>(&ka[c >> 1]) + 16 * (c & 1), &w, 16);
     };
+    // 8-byte piece idx (0 .. 4 DVB - 1) of the V^T operands of the tile at VBYTE: column block b = idx / 4 (kept in
+    // va[b % 2]), key group idx % 4
     auto load_v = [&](auto vbyte_tag, int idx) {
         constexpr int VBYTE = decltype(vbyte_tag)::value;
-        const int ks = idx / DVB, b = idx % DVB;
-        va[idx] = lds_read_tr8((lds + voff[b]) + (VBYTE + (ks * 16) * RB));
+        const int b = idx / 4, t = idx % 4;
+        const long w = lds_read_tr8((lds + voff[b]) + (VBYTE + (t * 16) * RB));
+        __builtin_memcpy(reinterpret_cast<char *>(&va[b]) + 8 * t, &w, 8);
     };
-    auto phase_a = [&](auto do_s_tag, auto vbyte_tag, f32x16 &Sacc, const f32x16 &Sexp, unsigned *pw) {
+    // phases A and C: Sacc = K Q^T from ka (if DO_S)  ||  pw = exp2(Sexp - m); pieces V0 .. V0 + 3 of V^T;
+    // each ka[u] is refilled with the operand of the block at KBYTE once its instruction has been issued (if DO_K)
+    auto phase_s = [&](auto do_s_tag, auto do_k_tag, auto vbyte_tag, auto v0_tag, auto kbyte_tag, f32x16 &Sacc,
+                       const f32x16 &Sexp, auto w0_tag) {
         constexpr bool DO_S = decltype(do_s_tag)::value;
+        constexpr bool DO_K = decltype(do_k_tag)::value;
+        constexpr int V0 = decltype(v0_tag)::value;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
+        for (int u = 0; u < KU; ++u) {
             if (DO_S) {
-                if (s == 0) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) Sacc[i] = 0.f;
-                }
-                Sacc = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(ka[s], qreg[s], Sacc, 0, 0, 0);
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                Sacc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ka[u], qreg[u], u == 0 ? zero : Sacc, 0, 0, 0, 0, 0,
+                                                                       0);
             }
             ATT_FENCE
 #pragma unroll
-            for (int idx = (2 * NPV * s) / KS; idx < (2 * NPV * (s + 1)) / KS && idx < NPV; ++idx)
-                load_v(vbyte_tag, idx);
+            for (int idx = V0 + (8 * u) / KU; idx < V0 + (8 * (u + 1)) / KU; ++idx) load_v(vbyte_tag, idx);
+            if (DO_K) {
 #pragma unroll
-            for (int op = (NOPS * s) / KS; op < (NOPS * (s + 1)) / KS; ++op) exp_op(Sexp, pw, op);
+                for (int c = 2 * u; c < 2 * u + 2; ++c) load_k(kbyte_tag, c);
+            }
+#pragma unroll
+            for (int op = (NOPS * u) / KU; op < (NOPS * (u + 1)) / KU; ++op) exp_op(Sexp, w0_tag, op);
             ATT_FENCE
         }
     };
-    auto phase_b = [&](auto do_max_tag, auto do_k_tag, auto kbyte_tag, const unsigned *pr, const f32x16 &Snext) {
+    auto block_max = [&](const f32x16 &S) {
+        float mx = max2_raw(fmaxf(S[0], S[1]), S[2]);
+#pragma unroll
+        for (int c = 1; c < 7; ++c) mx = max3_raw(mx, S[2 * c + 1], S[2 * c + 2]);
+        return max2_raw(mx, S[15]);
+    };
+    // phase D: O^T += V^T P^T, l += 1^T P^T  ||  maximum of Snext and the decision (if DO_MAX).  The V^T operands
+    // of column blocks 0 and 1 are there; those of blocks 2 and 3 are read into the same registers once the
+    // instructions that use them have been issued.  The row-sum instruction goes LAST and its result is read at
+    // the end of the phase: matrix instructions complete in order, so once that read is allowed every accumulator
+    // of the tile has been written.  (Without it, the register copies the compiler places on the way out of the
+    // tile loop read an accumulator that the last instruction is still writing: the wait states the compiler
+    // inserts for that cover one basic block, not the branches out of the loop.)
+    auto phase_pv = [&](auto do_max_tag, auto vbyte_tag, const f32x16 &Snext) {
         constexpr bool DO_MAX = decltype(do_max_tag)::value;
-        constexpr bool DO_K = decltype(do_k_tag)::value;
-        constexpr int HB = NPV / 2;
+        static_assert(DVB == 4, "two operand registers serve four column blocks");
         float mx = -INFINITY;
+        rescale_if_needed();
 #pragma unroll
-        for (int idx = 0; idx < NPV; ++idx) {
-            long pb;
-            __builtin_memcpy(&pb, pr + 2 * (idx / DVB), 8);
-            oacc[idx % DVB] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(va[idx], pb, oacc[idx % DVB], 0, 0, 0);
-            if (idx % DVB == DVB - 1) lacc = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(ones, pb, lacc, 0, 0, 0);
-            ATT_FENCE
-            if (DO_K) {
-#pragma unroll
-                for (int u = (KP * idx) / NPV; u < (KP * (idx + 1)) / NPV; ++u) load_k(kbyte_tag, u);
+        for (int b = 0; b < DVB; ++b) {
+            oacc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[b], pw, oacc[b], 0, 0, 0, 0, 0, 0);
+            if (b == DVB - 1) {                 // every accumulator = the tile's row sum of this lane's query
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                lt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pw, zero, 0, 0, 0, 0, 0, 0);
             }
-            if (DO_MAX && idx < HB) {
+            ATT_FENCE
+            if (DO_MAX && b >= 2) {             // in the shadow of the last three instructions
 #pragma unroll
-                for (int c = (8 * idx) / HB; c < (8 * (idx + 1)) / HB; ++c) {
+                for (int c = 4 * (b - 2); c < 4 * (b - 1); ++c) {
                     if (c == 0) mx = max2_raw(fmaxf(Snext[0], Snext[1]), Snext[2]);
                     else if (c < 7) mx = max3_raw(mx, Snext[2 * c + 1], Snext[2 * c + 2]);
                     else mx = max2_raw(mx, Snext[15]);
                     ATT_PIN(mx)
                 }
-                if (idx == HB - 1) decide(mx);
+                if (b == DVB - 1) decide(mx);
             }
             ATT_FENCE
         }
-        if (DO_MAX && any_upd) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) lacc[i] *= alpha;
-#pragma unroll
-            for (int b = 0; b < DVB; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-        }
+        l_run += lt[0];
+        // The compiler's wait states for this 16-pass instruction are two short of what the hardware needs before
+        // the LAST result registers may be touched (measured: 20, inserted: 18), so nothing may read an
+        // accumulator, or reuse a register of lt, right at that limit: four more wait states here, and lt stays
+        // claimed until the next tile has started (see the tile loop).
+        asm volatile("s_nop 3" : "+v"(lt));
     };
     using T = std::true_type;
     using F = std::false_type;
 
-    // ---- prologue: S of block 0 of tile 0, its maximum, K operands of block 1
+    // ---- prologue: scores of block 0 of tile 0 and their level, K operands of block 1
     if (wave_active && ntile > 0) {
 #pragma unroll
-        for (int u = 0; u < KP; ++u) load_k(std::integral_constant<int, 0>{}, u);
+        for (int c = 0; c < 2 * KU; ++c) load_k(std::integral_constant<int, 0>{}, c);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s0[i] = 0.f;
+        for (int u = 0; u < KU; ++u) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s0 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ka[u], qreg[u], u == 0 ? zero : s0, 0, 0, 0, 0, 0, 0);
+        }
 #pragma unroll
-        for (int s = 0; s < KS; ++s) s0 = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(ka[s], qreg[s], s0, 0, 0, 0);
-#pragma unroll
-        for (int u = 0; u < KP; ++u) load_k(std::integral_constant<int, 32 * RB>{}, u);
+        for (int c = 0; c < 2 * KU; ++c) load_k(std::integral_constant<int, 32 * RB>{}, c);
         if (L < 32) mask_block(s0, 0, L);
         float mx = fmaxf(fmaxf(s0[0], s0[1]), s0[2]);
 #pragma unroll
         for (int i = 3; i < 16; ++i) mx = fmaxf(mx, s0[i]);
-        decide(mx);                             // key 0 exists: the maximum is finite; nothing to rescale yet
+        decide(mx);                             // key 0 exists: the maximum is finite
+        m_acc = m_run;                          // the accumulators are zero: nothing to rescale
     }
 
 #define ATT_TILE(BUF, HAS_NEXT)                                                            \
@@ -462,15 +514,22 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
             if (kt + NSTG + 1 < ntile) { ATT_ROWS(kt + NSTG + 1) }                         \
         }                                                                                  \
         if (wave_active) {                                                                 \
+            asm volatile("" : "+v"(lt));            /* the registers of the last row sum are free from here on */ \
             using HN = std::integral_constant<bool, HAS_NEXT>;                             \
             constexpr int KB_ = ((BUF + 1) % NSTG) * TILE_B, VB_ = NSTG * TILE_B + BUF * TILE_B; \
-            phase_a(T{}, std::integral_constant<int, VB_>{}, s1, s0, pw0);                 \
+            using VB = std::integral_constant<int, VB_>;                                   \
+            phase_s(T{}, HN{}, VB{}, std::integral_constant<int, 0>{}, std::integral_constant<int, KB_>{}, s1, s0, \
+                    std::integral_constant<int, 0>{});                                     \
             if (!HAS_NEXT) mask_block(s1, 32, L - kt * ATT_BN);                            \
-            phase_b(T{}, HN{}, std::integral_constant<int, KB_>{}, pw0, s1);               \
-            phase_a(HN{}, std::integral_constant<int, VB_ + 32 * RB>{}, s0, s1, pw1);      \
+            decide(block_max(s1));                                                         \
+            if (any_upd) {                      /* rare: block 0 again, under the level both blocks share */ \
+                _Pragma("unroll") for (int op = 0; op < NOPS; ++op) exp_op(s0, std::integral_constant<int, 0>{}, op); \
+            }                                                                              \
+            phase_s(HN{}, HN{}, VB{}, std::integral_constant<int, 8>{},                    \
+                    std::integral_constant<int, KB_ + 32 * RB>{}, s0, s1, std::integral_constant<int, 4>{}); \
             if (HAS_NEXT && kt + 2 == ntile && L - (kt + 1) * ATT_BN < 32)                 \
                 mask_block(s0, 0, L - (kt + 1) * ATT_BN);                                  \
-            phase_b(HN{}, HN{}, std::integral_constant<int, KB_ + 32 * RB>{}, pw1, s0);    \
+            phase_pv(HN{}, VB{}, s0);                                                      \
         }                                                                                  \
         ++kt;                                                                              \
     }
@@ -492,13 +551,14 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 #undef ATT_OFFS
 #undef ATT_FETCH
 
-    // ---- epilogue: every accumulator of lacc holds the whole row sum of this lane's query
+    // ---- epilogue: l_run is the whole row sum of this lane's query (both lane halves hold it)
+    asm volatile("s_nop 7" : "+v"(lt));         // (see phase D: margin before the accumulators are read)
     {
         const int rl = wave * 32 + col;
         if (rl < nrows) {
             const int r = row0 + rl;
             const size_t dst = (size_t)h * N + (perm_q ? perm_q[(size_t)h * N + r] : r);
-            const float l_tot = lacc[0];
+            const float l_tot = l_run;
             const float inv = (l_tot > 0.f) ? scale_v[h] / l_tot : 0.f;
 #pragma unroll
             for (int b = 0; b < DVB; ++b)

@@ -222,3 +222,22 @@ def test_fp8_entry_points_reject_what_they_do_not_support(svg2):
     c128 = torch.zeros((1, 4, 128), dtype=torch.float32, device="cuda")
     with pytest.raises(Svg2Error, match="SVG2_BF16"):
         svg2.svg2_forward_fp8(x32, x32, x32, c128, c128.clone(), 0.9, 1)
+
+
+def test_sparse_attn_fp8_is_reproducible_run_to_run(svg2):
+    # the kernel has no atomics and a fixed summation order: repeated launches must give the same bits
+    # (a missing wait between a matrix instruction and a vector instruction shows up here as rare differences)
+    w = wl.WORKLOADS["small"]
+    heads = [0, 5]
+    Q, K, V, cq, ck = head_inputs(w, heads)
+    Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
+    a = svg2.svg2_forward(Qd, Kd, Vd, to_dev(cq), to_dev(ck), w.top_p, w.iters, want_aux=True).aux
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, Qd, Kd, Vd)
+    outs = []
+    for _ in range(4):
+        r = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, a.offsets_q, a.offsets_k, a.row_ptr, a.col_idx,
+                                      a.perm_q, a.perm_k, want_lse=True)
+        torch.cuda.synchronize()
+        outs.append((r.O.clone(), r.lse.clone()))
+    for O, lse in outs[1:]:
+        assert torch.equal(O, outs[0][0]) and torch.equal(lse, outs[0][1])
