@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 from paper_2505_18875_amd import workloads as wl  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak
+FP8_MFMA_PEAK_TFLOPS = 5000.0           # MI355X dense fp8 MFMA peak
 # HBM-side bytes per attention-kernel launch on the Wan-like layer at top-p 0.9, from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy in the
 # same runs): profiles/wan_like_attention_hbm_traffic.md.  Other workloads report null.
@@ -125,6 +126,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--gather-free", action="store_true",
                     help="time svg2_forward_gather_free (no permuted copies of Q, K, V) instead of svg2_forward")
+    ap.add_argument("--fp8", action="store_true",
+                    help="time svg2_forward_fp8 (attention step on E4M3 copies of Q, K, V; the paper's '+ FP8' variant) "
+                         "-- a reduced-precision mode, reported beside the bf16 headline, never instead of it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -168,13 +172,14 @@ def main():
     cqs = [cq0.clone() for _ in range(total + 1)]
     cks = [ck0.clone() for _ in range(total + 1)]
     O = torch.empty_like(Q)
-    ws = torch.empty(svg2.svg2_forward_workspace_size(svg2.SVG2_BF16, H, N, d, w.Cq, w.Ck, args.gather_free),
+    ws = torch.empty(svg2.svg2_forward_workspace_size(svg2.SVG2_BF16, H, N, d, w.Cq, w.Ck, args.gather_free, args.fp8),
                      dtype=torch.uint8, device="cuda")
-    log("workspace %.2f GB (%s)" % (ws.numel() / 1e9, "gather-free" if args.gather_free else "physical permutation"))
+    mode = "fp8 attention, gather-free" if args.fp8 else "gather-free" if args.gather_free else "physical permutation"
+    log("workspace %.2f GB (%s)" % (ws.numel() / 1e9, mode))
 
     def step(i, aux=False):
         return svg2.svg2_forward(Q, K, V, cqs[i], cks[i], w.top_p, w.iters, out=O, ws=ws, want_aux=aux,
-                                 gather_free=args.gather_free)
+                                 gather_free=args.gather_free, fp8=args.fp8)
 
     r = step(total, aux=True)                 # an extra, untimed pass that also reports the density
     torch.cuda.synchronize()
@@ -201,19 +206,25 @@ def main():
     sel_flops = dense_flops * float(density.mean())            # 4 d sum_sel |Q_i||K_j| over all heads
     attn_ms = stage_ms["attn"]
     achieved = sel_flops / (attn_ms * 1e-3) / 1e12
+    peak = FP8_MFMA_PEAK_TFLOPS if args.fp8 else BF16_MFMA_PEAK_TFLOPS
     out = {
         "metric": "effective TFLOP/s of one SVG2 layer (kmeans+permute+topp+sparse-attn), 4*H*N^2*d / layer time, "
                   "at N=75,600, H=40; ms/layer is ms_per_step",
         "value": dense_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3 attention operands (fp32 softmax and accumulation), bf16 elsewhere" if args.fp8 else "bf16",
+        "data": "synthetic",
         "config": {"workload": w.name, "H": H, "N": N, "d": d, "Cq": w.Cq, "Ck": w.Ck, "kmeans_iters": w.iters,
                    "top_p": w.top_p, "density": float(density.mean()),
-                   "entry_point": "svg2_forward_gather_free" if args.gather_free else "svg2_forward"},
+                   "entry_point": "svg2_forward_fp8" if args.fp8 else
+                                  "svg2_forward_gather_free" if args.gather_free else "svg2_forward"},
         "stages_ms": stage_ms,
-        "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": achieved,
-                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get((w.name, w.top_p)) if w.iters == wl.WORKLOADS[w.name].iters else None, "flops_per_launch": sel_flops, "ms_per_launch": attn_ms},
+        "roofline": {"kernel": "attn_fp8_kernel" if args.fp8 else "attn_bf16_kernel", "bound": "mfma",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None if args.fp8 or w.iters != wl.WORKLOADS[w.name].iters
+                     else ATTN_TRAFFIC_BYTES.get((w.name, w.top_p)),
+                     "flops_per_launch": sel_flops, "ms_per_launch": attn_ms},
     }
 
     if not args.no_dense:
@@ -221,7 +232,7 @@ def main():
         one = torch.tensor([[0, N]] * H, dtype=torch.int32, device="cuda")
         rp = torch.tensor([[0, 1]] * H, dtype=torch.int32, device="cuda")
         ci = torch.zeros((H, 1), dtype=torch.int32, device="cuda")
-        wsd = ws if not args.gather_free else None   # (the gather-free workspace may be smaller than this call needs)
+        wsd = ws if not (args.gather_free or args.fp8) else None   # (those workspaces may be smaller than this call needs)
         svg2.svg2_sparse_attn(Q, K, V, one, one, rp, ci, None, out=O, ws=wsd)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

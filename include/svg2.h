@@ -299,8 +299,8 @@ int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C,
  * at most SVG2_PROFILE_MAX_CALLS calls are kept, later ones go unrecorded).
  * svg2_profile_read waits for the recorded events, writes the summed
  * milliseconds per stage to stage_ms (HOST array of SVG2_N_STAGES floats, in
- * the order k-means Q, k-means K, permutation Q+K, selection, attention plan,
- * attention kernel) and the number of recorded calls to n_calls (HOST), then
+ * the order k-means Q, k-means K, permutation Q+K (svg2_forward_fp8: plus the
+ * E4M3 quantisation of Q, K, V), selection, attention plan, attention kernel) and the number of recorded calls to n_calls (HOST), then
  * clears the record.  svg2_profile_enable(0) stops recording.
  * ------------------------------------------------------------------------- */
 #define SVG2_N_STAGES 6

@@ -361,7 +361,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         else if (k == 5) { t1 = __builtin_amdgcn_exp2f(t1); ATT_PIN(t1) }
         else if (k == 6) { t2 = __builtin_amdgcn_exp2f(t2); ATT_PIN(t2) }
         else if (k == 7) { t3 = __builtin_amdgcn_exp2f(t3); ATT_PIN(t3) }
-        else if (k == 8) { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, 0, false); ATT_PIN(tw) }
+        else if (k == 8) { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, tw, false); ATT_PIN(tw) }   // both halves get written
         else { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, tw, true); ATT_PIN(tw) pw[w] = tw; }
     };
     auto mask_block = [&](f32x16 &S, int base, int rem) {

@@ -6,8 +6,10 @@ figures; every number comes from the library's kernels through the C ABI):
   clusters   attention-kernel efficiency against C_q and C_k           (Appendix D.1, Figs. 8-9)
   seeding    k-means from k-means++ seeding until the labels settle, against the warm start from the
              previous step's centroids                                 (Section 4.3 / 5.3, Fig. 5a)
+  fp8        output error and speed of the E4M3 attention path against the bf16 path, both measured against
+             the fp32 kernel on the same selection                     (Table 1, "+ FP8" rows)
 
-Usage: python -m paper_2505_18875_amd.diagnostics {recall,clusters,seeding} [--workload wan_like] [--heads 8]
+Usage: python -m paper_2505_18875_amd.diagnostics {recall,clusters,seeding,fp8} [--workload wan_like] [--heads 8]
 """
 from __future__ import annotations
 
@@ -169,9 +171,50 @@ def seeding(args):
     print("| ratio cold / warm | %.0fx | the paper reports up to 76x for its centroid cache |" % ((t_seed + t_iter) / t_warm))
 
 
+def fp8(args):
+    import torch
+    import paper_2505_18875_amd as svg2
+    w = wl.WORKLOADS[args.workload]
+    if w.dtype != "bf16" or w.d != 128:
+        raise SystemExit("the FP8 path needs a bf16 workload with head dimension 128")
+    heads = list(range(args.heads))
+    Q, K, V, Qd, Kd, Vd = _inputs(w, heads)
+    kq = svg2.svg2_kmeans(Qd, _init(w, heads, Q, w.Cq, 0), w.iters)
+    kk = svg2.svg2_kmeans(Kd, _init(w, heads, K, w.Ck, 1), w.iters)
+    pq = svg2.svg2_permute(kq.labels, w.Cq)
+    pk = svg2.svg2_permute(kk.labels, w.Ck)
+    Qf, Kf, Vf = Qd.float(), Kd.float(), Vd.float()
+    t_q, q8 = _timed(lambda: [svg2.svg2_quantize_fp8(t) for t in (Qd, Kd, Vd)])
+    (Q8, sq), (K8, sk), (V8, sv) = q8
+    flops = 4.0 * len(heads) * float(w.N) ** 2 * w.d
+    print("E4M3 attention against bf16 attention, reference = the fp32 kernel on the same selection: %s, heads 0..%d"
+          % (w.name, args.heads - 1))
+    print("(quantising Q, K and V of these heads: %.3f ms)" % t_q)
+    print("\n| top-p | density | bf16 rel. rms err | bf16 min cosine | fp8 rel. rms err | fp8 min cosine | bf16 ms | fp8 ms | "
+          "fp8 TFLOP/s on selected | speed-up |\n|---|---|---|---|---|---|---|---|---|---|")
+
+    def err(O, ref):
+        O, ref = O.double(), ref.double()
+        rel = ((O - ref).pow(2).sum((1, 2)) / ref.pow(2).sum((1, 2))).sqrt().mean().item()
+        cos = torch.nn.functional.cosine_similarity(O, ref, dim=2).min().item()
+        return rel, cos
+    for p in (0.5, 0.9, 1.0):
+        sel = svg2.svg2_select_topp(kq.centroids, kk.centroids, kq.counts, kk.counts, p)
+        common = (pq.offsets, pk.offsets, sel.row_ptr, sel.col_idx, pq.perm, pk.perm)
+        ref = svg2.svg2_sparse_attn_gather_free(Qf, Kf, Vf, *common).O
+        t_b, ob = _timed(lambda: svg2.svg2_sparse_attn_gather_free(Qd, Kd, Vd, *common))
+        t_8, o8 = _timed(lambda: svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, *common))
+        torch.cuda.synchronize()
+        dens = sel.density.double().mean().item()
+        eb, e8 = err(ob.O, ref), err(o8.O, ref)
+        print("| %.2f | %.4f | %.4f | %.5f | %.4f | %.5f | %.2f | %.2f | %.0f | %.2fx |"
+              % (p, dens, eb[0], eb[1], e8[0], e8[1], t_b, t_8, flops * dens / t_8 / 1e9, t_b / t_8))
+        del ref, ob, o8
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=("recall", "clusters", "seeding"))
+    ap.add_argument("what", choices=("recall", "clusters", "seeding", "fp8"))
     ap.add_argument("--workload", default="wan_like", choices=sorted(wl.WORKLOADS))
     ap.add_argument("--heads", type=int, default=8)
     args = ap.parse_args()
@@ -180,7 +223,7 @@ def main():
     svg2.load_library()
     if not torch.cuda.is_available():
         raise RuntimeError("diagnostics need a GPU")
-    {"recall": recall, "clusters": clusters, "seeding": seeding}[args.what](args)
+    {"recall": recall, "clusters": clusters, "seeding": seeding, "fp8": fp8}[args.what](args)
 
 
 if __name__ == "__main__":
