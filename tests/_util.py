@@ -1,4 +1,6 @@
 """Helpers shared by the GPU parity tests: numpy <-> device tensors in the workload's storage type."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -51,3 +53,23 @@ def assert_label_disagreements_are_near_ties(svg2, oracle, X, X_dev, init, iters
         assert np.all(gap < 1e-3), "label disagreement away from a tie: gaps %s" % np.sort(gap)[-5:]
     assert bad.size <= 1e-3 * gpu_labels.size
     return int(bad.size)
+
+
+def upload_heads(w, heads):
+    """All requested heads of a bf16 workload as device tensors (Q, K, V) plus their seeded initial centroids."""
+    H = len(heads)
+    Q = torch.empty((H, w.N, w.d), dtype=torch.bfloat16, device="cuda")
+    K, V = torch.empty_like(Q), torch.empty_like(Q)
+    cq = torch.empty((H, w.Cq, w.d), dtype=torch.float32, device="cuda")
+    ck = torch.empty((H, w.Ck, w.d), dtype=torch.float32, device="cuda")
+
+    def gen(i):
+        h = heads[i]
+        q, k, v = wl.make_head(w, h)
+        return i, q, k, v, wl.init_centroids(w, h, q, w.Cq, 0), wl.init_centroids(w, h, k, w.Ck, 1)
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for i, q, k, v, a, b in ex.map(gen, range(H)):
+            Q[i], K[i], V[i] = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+            cq[i], ck[i] = to_dev(a), to_dev(b)
+    return Q, K, V, cq, ck

@@ -241,3 +241,30 @@ def test_sparse_attn_fp8_is_reproducible_run_to_run(svg2):
         outs.append((r.O.clone(), r.lse.clone()))
     for O, lse in outs[1:]:
         assert torch.equal(O, outs[0][0]) and torch.equal(lse, outs[0][1])
+
+
+def test_forward_fp8_wan_like_full_size(svg2, oracle):
+    # the benchmark's shape and launch configuration (H = 40, N = 75,600): the whole layer once, then two heads against
+    # the oracle on their quantised operands, on a seeded sample of query rows
+    from _util import upload_heads
+    w = wl.WORKLOADS["wan_like"]
+    heads = list(range(w.H))
+    Q, K, V, cq, ck = upload_heads(w, heads)
+    cq2, ck2 = cq.clone(), ck.clone()
+    ref = svg2.svg2_forward(Q, K, V, cq, ck, w.top_p, w.iters, want_aux=True)
+    res = svg2.svg2_forward_fp8(Q, K, V, cq2, ck2, w.top_p, w.iters, want_aux=True)
+    torch.cuda.synchronize()
+    a = res.aux
+    for n in ("labels_q", "labels_k", "perm_q", "perm_k", "row_ptr", "density"):
+        assert torch.equal(getattr(a, n), getattr(ref.aux, n)), n
+    assert bool(torch.isfinite(res.O.float()).all())
+    for h in (0, 39):
+        q, k, v = to_np(Q[h]), to_np(K[h]), to_np(V[h])
+        rows = np.sort(np.random.default_rng(h).choice(w.N, 128, replace=False)).astype(np.int32)
+        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, q, k, v, a, h, w.d, rows)
+        _check_against(to_np(res.O[h]).astype(np.float64), to_np(a.lse[h]).astype(np.float64), O_ref, lse_ref,
+                       pq[rows], np.abs(v).max())
+    # against the bf16 layer on the same selection: the operands' rounding, a loose sanity bound
+    d = (res.O.float() - ref.O.float())
+    rel = (d.pow(2).sum((1, 2)) / ref.O.float().pow(2).sum((1, 2))).sqrt()
+    assert float(rel.max()) < 0.3

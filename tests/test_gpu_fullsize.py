@@ -8,14 +8,12 @@ labels / centroids), and the attention output on a seeded sample of query rows
 case does the same for two heads of the Hunyuan-like shape (N = 118,800) and a
 third steps through a warm-started denoising sequence.
 """
-from concurrent.futures import ThreadPoolExecutor
-
 import numpy as np
 import pytest
 import torch
 
 from paper_2505_18875_amd import workloads as wl
-from _util import assert_label_disagreements_are_near_ties, to_dev, to_np
+from _util import assert_label_disagreements_are_near_ties, to_dev, to_np, upload_heads as _upload
 
 pytestmark = pytest.mark.gpu
 
@@ -29,26 +27,6 @@ def svg2():
 
 def _csr_rows(row_ptr, col_idx):
     return [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in range(len(row_ptr) - 1)]
-
-
-def _upload(w, heads):
-    """All requested heads as bf16 device tensors; host copies are kept only for `keep`."""
-    H = len(heads)
-    Q = torch.empty((H, w.N, w.d), dtype=torch.bfloat16, device="cuda")
-    K, V = torch.empty_like(Q), torch.empty_like(Q)
-    cq = torch.empty((H, w.Cq, w.d), dtype=torch.float32, device="cuda")
-    ck = torch.empty((H, w.Ck, w.d), dtype=torch.float32, device="cuda")
-
-    def gen(i):
-        h = heads[i]
-        q, k, v = wl.make_head(w, h)
-        return i, q, k, v, wl.init_centroids(w, h, q, w.Cq, 0), wl.init_centroids(w, h, k, w.Ck, 1)
-
-    with ThreadPoolExecutor(max_workers=8) as ex:
-        for i, q, k, v, a, b in ex.map(gen, range(H)):
-            Q[i], K[i], V[i] = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
-            cq[i], ck[i] = to_dev(a), to_dev(b)
-    return Q, K, V, cq, ck
 
 
 def _check_heads(svg2, oracle, w, heads, check, Q, K, V, cq0, res, cq_out, ck_out, iters, n_rows, warm=None,
