@@ -261,7 +261,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 
     // ---- loader: as in the bf16 kernel (rows looked up by one wavefront, global -> LDS directly)
     const int32_t *pkh = perm_k ? perm_k + (size_t)h * N : nullptr;
-    int cur = 0;
+    int cur = 0, row_pend = 0;
     const int ld_row = lane / CPR;
     const int ld_r = wave * RPI + ld_row;       // tile row modulo 32 (load pass p adds 32 p)
     const unsigned ld_koff = (unsigned)(((lane % CPR) ^ ((ld_r >> 1) & 7)) * 16);
@@ -275,6 +275,17 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         if (perm_k) row_ = pkh[row_];                                                      \
         s_rows[((KT) & 1) * ATT_BN + lane] = row_ * RB;                                    \
     }
+// The same in two steps, for the tile loop: the look-up (and, gather-free, the load of the token index) is issued
+// at the top of a tile, the result is parked in s_rows at the bottom, when that load has long landed -- waiting
+// for it at the top would also wait for the tile fetches issued just before it (loads retire in order).
+#define ATT_ROWS_ISSUE(KT)                                                                 \
+    if (wave == ((KT) & (NW - 1))) {                                                       \
+        const int kk = (KT) * ATT_BN + lane;                                               \
+        row_pend = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
+        if (perm_k) row_pend = pkh[row_pend];                                              \
+    }
+#define ATT_ROWS_COMMIT(KT)                                                                \
+    if (wave == ((KT) & (NW - 1))) s_rows[((KT) & 1) * ATT_BN + lane] = row_pend * RB;
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
         OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
@@ -511,7 +522,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
                 ATT_OFFS(kt + NSTG, off_nx)                                                \
                 ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
             }                                                                              \
-            if (kt + NSTG + 1 < ntile) { ATT_ROWS(kt + NSTG + 1) }                         \
+            if (kt + NSTG + 1 < ntile) { ATT_ROWS_ISSUE(kt + NSTG + 1) }                   \
         }                                                                                  \
         if (wave_active) {                                                                 \
             asm volatile("" : "+v"(lt));            /* the registers of the last row sum are free from here on */ \
@@ -531,6 +542,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
                 mask_block(s0, 0, L - (kt + 1) * ATT_BN);                                  \
             phase_pv(HN{}, VB{}, s0);                                                      \
         }                                                                                  \
+        if (HAS_NEXT && kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }          \
         ++kt;                                                                              \
     }
     static_assert(NSTG == 2, "the tile loop is unrolled by the number of buffers");
@@ -548,6 +560,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 #undef ATT_FENCE
 #undef ATT_PIN
 #undef ATT_ROWS
+#undef ATT_ROWS_ISSUE
+#undef ATT_ROWS_COMMIT
 #undef ATT_OFFS
 #undef ATT_FETCH
 
