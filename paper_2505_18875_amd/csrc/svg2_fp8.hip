@@ -173,7 +173,8 @@ __device__ __forceinline__ long lds_read_tr8(const lds_u8 *p)
     return r;
 }
 
-static constexpr int F8_NSTG = 2;           // K and V tile buffers in LDS (each)
+static constexpr int F8_NSTG = 2;           // K and V tile buffers in LDS (each): 2 or 3.  Measured on the Wan-like layer
+                                            // (8-head probe, ms sparse / dense): 2 buffers 5.08 / 14.9, 3 buffers 5.30 / 15.6
 static constexpr float F8_HEADROOM = 8.0f;  // a score may exceed the reference level by 2^8 before it moves
 static constexpr float F8_LEVEL = 6.0f;     // the reference level is put 2^6 below the block maximum
 
@@ -276,16 +277,24 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         s_rows[((KT) & 1) * ATT_BN + lane] = row_ * RB;                                    \
     }
 // The same in two steps, for the tile loop: the look-up (and, gather-free, the load of the token index) is issued
-// at the top of a tile, the result is parked in s_rows at the bottom, when that load has long landed -- waiting
-// for it at the top would also wait for the tile fetches issued just before it (loads retire in order).
+// at the top of a tile BEFORE the tile fetches, the result is parked in s_rows at the bottom.  Loads retire in
+// order, so the index has arrived once at most the 2 NPASS fetch instructions issued after it are outstanding
+// (a look-up is only issued when both fetches of that tile top are); waiting for everything would stall on
+// fetches that are meant to stay in flight.  The load is an asm statement so that this wait can be written by hand.
 #define ATT_ROWS_ISSUE(KT)                                                                 \
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
         row_pend = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
-        if (perm_k) row_pend = pkh[row_pend];                                              \
+        if (perm_k) {                                                                      \
+            const int32_t *src_ = pkh + row_pend;                                          \
+            asm volatile("global_load_dword %0, %1, off" : "=v"(row_pend) : "v"(src_) : "memory"); \
+        }                                                                                  \
     }
 #define ATT_ROWS_COMMIT(KT)                                                                \
-    if (wave == ((KT) & (NW - 1))) s_rows[((KT) & 1) * ATT_BN + lane] = row_pend * RB;
+    if (wave == ((KT) & (NW - 1))) {                                                       \
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(row_pend) : "n"(2 * NPASS));             \
+        s_rows[((KT) & 1) * ATT_BN + lane] = row_pend * RB;                                \
+    }
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
         OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
@@ -307,10 +316,19 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     if (ntile > 1) {
         ATT_OFFS(1, off_nx)
         ATT_FETCH(off_nx, Kb, ld_koff, sK + TILE_B)
+        if (NSTG > 2) { ATT_FETCH(off_nx, Vb, ld_voff, sV + TILE_B) }
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
-    // off_nx stays live: the rows of tile 1, whose V is requested at the top of tile 0
+    if (NSTG > 2) {
+        if (ntile > 3) { ATT_ROWS(3) }
+        __syncthreads();
+        if (ntile > 2) {
+            ATT_OFFS(2, off_nx)
+            ATT_FETCH(off_nx, Kb, ld_koff, sK + 2 * TILE_B)
+        }
+    }
+    // off_nx stays live: the rows of tile NSTG - 1, whose V is requested at the top of tile 0
 
     // per-lane LDS read addresses (buffer 0): the two 16-byte halves of K operand u, V^T operand of column block b
     int koff[2 * KU], voff[DVB];
@@ -355,10 +373,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = 0x38383838;          // E4M3 1.0
     f32x16 s0, s1;
-    i32x8 pw;                                   // probabilities of the tile: words 0..3 block 0, 4..7 block 1
+    int pw[8];                                  // probabilities of the tile: words 0..3 block 0, 4..7 block 1
     i32x8 ka[KU], va[DVB];                      // K operands of the next score block, V^T operands of this tile
     float m_acc = 0.f, t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
-    int tw = 0;
+    for (int i = 0; i < 8; ++i) pw[i] = 0;
     f32x16 lt = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // row sums of the tile just accumulated
     bool any_upd = false;
 
@@ -372,8 +390,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         else if (k == 5) { t1 = __builtin_amdgcn_exp2f(t1); ATT_PIN(t1) }
         else if (k == 6) { t2 = __builtin_amdgcn_exp2f(t2); ATT_PIN(t2) }
         else if (k == 7) { t3 = __builtin_amdgcn_exp2f(t3); ATT_PIN(t3) }
-        else if (k == 8) { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, tw, false); ATT_PIN(tw) }   // both halves get written
-        else { tw = __builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, tw, true); ATT_PIN(tw) pw[w] = tw; }
+        else if (k == 8) { pw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, pw[w], false); ATT_PIN(pw[w]) }   // both halves get written
+        else { pw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, pw[w], true); ATT_PIN(pw[w]) }
     };
     auto mask_block = [&](f32x16 &S, int base, int rem) {
 #pragma unroll
@@ -463,12 +481,13 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         static_assert(DVB == 4, "two operand registers serve four column blocks");
         float mx = -INFINITY;
         rescale_if_needed();
+        const i32x8 pb = {pw[0], pw[1], pw[2], pw[3], pw[4], pw[5], pw[6], pw[7]};
 #pragma unroll
         for (int b = 0; b < DVB; ++b) {
-            oacc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[b], pw, oacc[b], 0, 0, 0, 0, 0, 0);
+            oacc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va[b], pb, oacc[b], 0, 0, 0, 0, 0, 0);
             if (b == DVB - 1) {                 // every accumulator = the tile's row sum of this lane's query
                 const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                lt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pw, zero, 0, 0, 0, 0, 0, 0);
+                lt = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pb, zero, 0, 0, 0, 0, 0, 0);
             }
             ATT_FENCE
             if (DO_MAX && b >= 2) {             // in the shadow of the last three instructions
@@ -514,15 +533,17 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 
 #define ATT_TILE(BUF, HAS_NEXT)                                                            \
     {                                                                                      \
-        __builtin_amdgcn_s_waitcnt(0x0F70);                                                \
+        /* the fetches issued NSTG - 1 tiles ago (V of this tile, K of the next) must have landed */ \
+        if (NSTG > 2 && kt + NSTG - 1 < ntile) __builtin_amdgcn_s_waitcnt(0x0F70 | ((NSTG - 2) * 2 * NPASS)); \
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
         __syncthreads();                                                                   \
         if (HAS_NEXT) {                                                                    \
+            if (kt + NSTG + 1 < ntile) { ATT_ROWS_ISSUE(kt + NSTG + 1) }                   \
             if (kt + NSTG - 1 < ntile) { ATT_FETCH(off_nx, Vb, ld_voff, sV + ((BUF + NSTG - 1) % NSTG) * TILE_B) } \
             if (kt + NSTG < ntile) {                                                       \
                 ATT_OFFS(kt + NSTG, off_nx)                                                \
                 ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
             }                                                                              \
-            if (kt + NSTG + 1 < ntile) { ATT_ROWS_ISSUE(kt + NSTG + 1) }                   \
         }                                                                                  \
         if (wave_active) {                                                                 \
             asm volatile("" : "+v"(lt));            /* the registers of the last row sum are free from here on */ \
@@ -545,16 +566,22 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         if (HAS_NEXT && kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }          \
         ++kt;                                                                              \
     }
-    static_assert(NSTG == 2, "the tile loop is unrolled by the number of buffers");
+    static_assert(NSTG == 2 || NSTG == 3, "the tile loop is unrolled by the number of buffers");
     int kt = 0;
     while (kt < ntile - 1) {
         ATT_TILE(0, true)
         if (kt >= ntile - 1) break;
         ATT_TILE(1, true)
+        if constexpr (NSTG == 3) {
+            if (kt >= ntile - 1) break;
+            ATT_TILE((NSTG - 1), true)
+        }
     }
     if (ntile > 0) {
-        if (kt % NSTG == 0) ATT_TILE(0, false)
-        else ATT_TILE(1, false)
+        const int bl = kt % NSTG;
+        if (bl == 0) ATT_TILE(0, false)
+        else if (bl == 1) ATT_TILE(1, false)
+        else if constexpr (NSTG == 3) ATT_TILE((NSTG - 1), false)
     }
 #undef ATT_TILE
 #undef ATT_FENCE
