@@ -47,7 +47,8 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
                                                         const int32_t *__restrict__ col_idx, int Cq, int Ck, int BM,
                                                         int max_tiles, int4 *__restrict__ tiles,
                                                         int32_t *__restrict__ n_tiles, int2 *__restrict__ runs,
-                                                        int32_t *__restrict__ row_keys)
+                                                        int32_t *__restrict__ row_keys,
+                                                        int32_t *__restrict__ cl_first)
 {
     __shared__ int32_t s_wave[4];
     __shared__ int32_t s_carry;
@@ -76,6 +77,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
         int base = s_carry;
         for (int w = 0; w < wave; ++w) base += s_wave[w];
         const int first = base + incl - nt;
+        if (c < Cq) cl_first[(size_t)h * Cq + c] = first;
         for (int t = 0; t < nt; ++t)
             tiles[(size_t)h * max_tiles + first + t] = make_int4(c, start + t * BM, min(BM, size - t * BM), 0);
         __syncthreads();
@@ -137,6 +139,70 @@ __global__ __launch_bounds__(256) void attn_tile_base_kernel(const int32_t *__re
     if (tid == 0) tile_base[H] = s_carry;
 }
 
+// order[0 .. all tiles): the work items sorted by decreasing number of key tiles (longest first), so that the
+// last workgroups of a launch are short ones.  The tiles of one query cluster stay together (they read the
+// same keys); among clusters of equal length the order is whatever the atomics give -- it only decides when a
+// work item runs, never what it computes.  One workgroup; with more clusters than ORD_MAX_CLUSTERS the list
+// keeps its head-major order.
+static constexpr int ORD_BUCKETS = 2048;
+static constexpr int ORD_MAX_CLUSTERS = 1 << 20;
+
+__global__ __launch_bounds__(1024) void attn_order_kernel(const int32_t *__restrict__ offsets_q,
+                                                          const int32_t *__restrict__ tile_base,
+                                                          const int32_t *__restrict__ row_keys,
+                                                          const int32_t *__restrict__ cl_first, int H, int Cq, int BM,
+                                                          int32_t *__restrict__ order)
+{
+    __shared__ int32_t s_cnt[ORD_BUCKETS];
+    __shared__ int32_t s_part[1024];
+    const int tid = threadIdx.x;
+    const long long ncl = (long long)H * Cq;
+    if (ncl > ORD_MAX_CLUSTERS) {
+        const int total = tile_base[H];
+        for (int v = tid; v < total; v += 1024) order[v] = v;
+        return;
+    }
+    for (int b = tid; b < ORD_BUCKETS; b += 1024) s_cnt[b] = 0;
+    __syncthreads();
+    auto bucket_of = [&](int i) {               // longest first: bucket 0 holds the clusters with the most key tiles
+        const int kt = (row_keys[i] + ATT_BN - 1) / ATT_BN;
+        return ORD_BUCKETS - 1 - min(kt, ORD_BUCKETS - 1);
+    };
+    auto tiles_of = [&](int i) {
+        const int h = i / Cq, c = i - h * Cq;
+        const int32_t *oq = offsets_q + (size_t)h * (Cq + 1);
+        return (oq[c + 1] - oq[c] + BM - 1) / BM;
+    };
+    for (int i = tid; i < (int)ncl; i += 1024) {
+        const int nt = tiles_of(i);
+        if (nt > 0) atomicAdd(&s_cnt[bucket_of(i)], nt);
+    }
+    __syncthreads();
+    // exclusive scan over the buckets: two per thread
+    const int a0 = s_cnt[2 * tid], a1 = s_cnt[2 * tid + 1];
+    s_part[tid] = a0 + a1;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int v = (tid >= o) ? s_part[tid - o] : 0;
+        __syncthreads();
+        s_part[tid] += v;
+        __syncthreads();
+    }
+    const int excl = s_part[tid] - (a0 + a1);
+    s_cnt[2 * tid] = excl;
+    s_cnt[2 * tid + 1] = excl + a0;
+    __syncthreads();
+    for (int i = tid; i < (int)ncl; i += 1024) {
+        const int nt = tiles_of(i);
+        if (nt > 0) {
+            const int h = i / Cq;
+            const int pos = atomicAdd(&s_cnt[bucket_of(i)], nt);
+            const int v0 = tile_base[h] + cl_first[i];
+            for (int t = 0; t < nt; ++t) order[pos + t] = v0 + t;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- bf16 MFMA kernel
 
 // acc + both bf16 halves of w (v_dot2c_f32_bf16 with a vector of ones): the row sum is taken
@@ -162,7 +228,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
-    int max_tiles,
+    const int32_t *__restrict__ order, int max_tiles,
     const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2, int group,
     bf16_t *__restrict__ O, float *__restrict__ lse)
 {
@@ -193,8 +259,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     // consecutive tiles per XCD, so tiles that share keys share an L2 and every XCD
     // gets the same amount of work whatever the per-head densities are.
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const int v = (slot / group) * (8 * group) + xcd * group + slot % group;
-    if (v >= tile_base[H]) return;
+    const int pos = (slot / group) * (8 * group) + xcd * group + slot % group;
+    if (pos >= tile_base[H]) return;
+    const int v = order[pos];                   // longest work items first (attn_order_kernel)
     int h = 0;
     for (int step = 1 << 15; step > 0; step >>= 1)
         if (h + step < H && tile_base[h + step] <= v) h += step;
@@ -674,6 +741,8 @@ size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
     c.take<int32_t>((size_t)H + 1);
     c.take<int2>((size_t)H * Cq * Ck);
     c.take<int32_t>((size_t)H * Cq);
+    c.take<int32_t>((size_t)H * Cq);
+    c.take<int32_t>((size_t)H * max_tiles);
     return c.used;
 }
 
@@ -683,8 +752,11 @@ int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *off
 {
     const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(H), dim3(256), 0, st, offsets_q, offsets_k, row_ptr, col_idx, Cq, Ck,
-                       attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys);
+                       attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys, a.cl_first);
     hipLaunchKernelGGL(attn_tile_base_kernel, dim3(1), dim3(256), 0, st, a.n_tiles, H, a.tile_base);
+    if (dtype == SVG2_BF16)                     // the fp32 kernel is launched on a (tile, head) grid and needs no list
+        hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(1024), 0, st, offsets_q, a.tile_base, a.row_keys,
+                           a.cl_first, H, Cq, attn_bm(dtype), a.order);
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
 }
@@ -716,13 +788,13 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
-                               tiles, tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
+                               tiles, tile_base, a.order, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         } else {
             auto kern = attn_bf16_kernel<64>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
-                               tiles, tile_base, max_tiles, runs, row_keys, scale_log2, group, o, lse);
+                               tiles, tile_base, a.order, max_tiles, runs, row_keys, scale_log2, group, o, lse);
         }
     } else {
         const float *q = static_cast<const float *>(Qp), *k = static_cast<const float *>(Kp),

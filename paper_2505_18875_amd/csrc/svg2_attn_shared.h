@@ -94,6 +94,8 @@ struct AttnWs {
     int32_t *n_tiles, *tile_base;
     int2 *runs;
     int32_t *row_keys;
+    int32_t *cl_first;                  // [H][Cq] first tile (inside its head) of every query cluster
+    int32_t *order;                     // [all tiles] work items, longest first
     int max_tiles;
 };
 
@@ -107,6 +109,8 @@ inline AttnWs attn_carve(void *ws, int dtype, int H, int N, int Cq, int Ck)
     a.tile_base = c.take<int32_t>((size_t)H + 1);
     a.runs = c.take<int2>((size_t)H * Cq * Ck);
     a.row_keys = c.take<int32_t>((size_t)H * Cq);
+    a.cl_first = c.take<int32_t>((size_t)H * Cq);
+    a.order = c.take<int32_t>((size_t)H * a.max_tiles);
     return a;
 }
 

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     const float *__restrict__ scale_q, const float *__restrict__ scale_k, const float *__restrict__ scale_v, int H,
     int N, int Cq, int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
-    int max_tiles, const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2_base,
+    const int32_t *__restrict__ order, int max_tiles, const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2_base,
     int group, bf16_t *__restrict__ O, float *__restrict__ lse)
 {
     static_assert(D == 128, "row = 128 bytes: the swizzles below are written for that");
@@ -210,8 +210,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 
     // work item: as in the bf16 kernel (one list of all tiles, ATT_GROUP consecutive tiles per XCD)
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const int v = (slot / group) * (8 * group) + xcd * group + slot % group;
-    if (v >= tile_base[H]) return;
+    const int pos = (slot / group) * (8 * group) + xcd * group + slot % group;
+    if (pos >= tile_base[H]) return;
+    const int v = order[pos];                   // longest work items first
     int h = 0;
     for (int step = 1 << 15; step > 0; step >>= 1)
         if (h + step < H && tile_base[h + step] <= v) h += step;
@@ -635,7 +636,7 @@ int attn_fp8_main_launch(const void *Q8, const void *K8, const void *V8, const f
                                        (int)lds));
     hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, static_cast<const uint8_t *>(Q8),
                        static_cast<const uint8_t *>(K8), static_cast<const uint8_t *>(V8), scale_q, scale_k, scale_v, H,
-                       N, Cq, Ck, row_ptr, perm_q, perm_k, a.tiles, a.tile_base, a.max_tiles, a.runs, a.row_keys,
+                       N, Cq, Ck, row_ptr, perm_q, perm_k, a.tiles, a.tile_base, a.order, a.max_tiles, a.runs, a.row_keys,
                        scale_log2, group, static_cast<bf16_t *>(O), lse);
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
