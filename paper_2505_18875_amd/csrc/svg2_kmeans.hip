@@ -36,31 +36,43 @@ static constexpr int KM_WG_TOKENS = KM_NW * KM_TB * 32;
 static constexpr int KM_IB = 8;        // token blocks per work item (bf16 kernel)
 static constexpr int KM_UB = 4;        // load instructions in flight per wavefront in the segmented sum
 static constexpr int KM_SEG = 256;     // rows per piece of the segmented sum
+static constexpr int KM_FULL_FIRST = 2; // iterations whose update step sums every cluster afresh ...
+static constexpr int KM_FULL_EVERY = 8; // ... and again every so many iterations (bounds the rounding drift of the delta update)
 
 // ---------------------------------------------------------------- finalize
-// grid (C, H), block d.  do_update = 0: centroids <- init (first call).
-// Cluster j owns pieces first_piece[j] .. first_piece[j+1] of the head.
+// grid (C, H), block d.  mode 0: centroids <- init (first call).  mode 1: cluster sum = sum of the cluster's
+// pieces (pieces first_piece[j] .. first_piece[j+1] of the head).  mode 2 (delta update): cluster sum = previous
+// cluster sum + the pieces of the tokens that joined the cluster (new sort order) - the pieces of the tokens that
+// left it (previous sort order).  The sums are kept in csum between iterations; an empty cluster keeps its
+// centroid and gets the sum 0.  All additions happen in a fixed order: reproducible bit for bit.
 template <bool BF16>
 __global__ void kmeans_finalize_kernel(const float *__restrict__ init, float *__restrict__ centroids,
                                        const float *__restrict__ psum, const int32_t *__restrict__ first_piece,
                                        const int32_t *__restrict__ offsets, int max_pieces, int C, int d,
                                        bf16_t *__restrict__ cb, float *__restrict__ cn,
-                                       int32_t *__restrict__ counts_out, int do_update)
+                                       int32_t *__restrict__ counts_out, int mode, float *__restrict__ csum,
+                                       const float *__restrict__ psum_old, const int32_t *__restrict__ first_piece_old)
 {
     __shared__ float s_red[2];
     const int j = blockIdx.x, h = blockIdx.y, k = threadIdx.x;
     const size_t idx = ((size_t)h * C + j) * d + k;
     float c;
-    if (do_update) {
+    if (mode != 0) {
         const int cnt = offsets[(size_t)h * (C + 1) + j + 1] - offsets[(size_t)h * (C + 1) + j];
+        const int p0 = first_piece[(size_t)h * (C + 1) + j], p1 = first_piece[(size_t)h * (C + 1) + j + 1];
+        float s = (mode == 2) ? csum[idx] : 0.f;
+        for (int q = p0; q < p1; ++q) s += psum[((size_t)h * max_pieces + q) * d + k];
+        if (mode == 2) {
+            const int o0 = first_piece_old[(size_t)h * (C + 1) + j], o1 = first_piece_old[(size_t)h * (C + 1) + j + 1];
+            for (int q = o0; q < o1; ++q) s -= psum_old[((size_t)h * max_pieces + q) * d + k];
+        }
         if (cnt > 0) {
-            const int p0 = first_piece[(size_t)h * (C + 1) + j], p1 = first_piece[(size_t)h * (C + 1) + j + 1];
-            float s = 0.f;
-            for (int q = p0; q < p1; ++q) s += psum[((size_t)h * max_pieces + q) * d + k];
             c = s / (float)cnt;
         } else {
+            s = 0.f;
             c = centroids[idx];
         }
+        csum[idx] = s;
         if (k == 0 && counts_out) counts_out[(size_t)h * C + j] = cnt;
     } else {
         c = init[idx];
@@ -407,6 +419,84 @@ __global__ __launch_bounds__(256) void kmeans_segsum_kernel(const T *__restrict_
     }
 }
 
+// The same over the rows of a piece whose label in `other` differs from the piece's cluster: with `other` = the
+// previous labels and the new sort order these are the tokens that JOINED the cluster in this iteration, with
+// `other` = the new labels and the previous sort order the tokens that LEFT it.  A wavefront first scans its piece
+// one row per lane and packs the rows that qualify into a list (in sorted order, so the sum keeps a fixed order),
+// then reads only those rows of X.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void kmeans_segsum_delta_kernel(const T *__restrict__ X,
+                                                                  const int32_t *__restrict__ perm,
+                                                                  const int32_t *__restrict__ other, int N,
+                                                                  int max_pieces, const int4 *__restrict__ pieces,
+                                                                  const int32_t *__restrict__ n_pieces,
+                                                                  float *__restrict__ psum)
+{
+    constexpr int EPL = 16 / sizeof(T);
+    constexpr int LPR = D / EPL;
+    constexpr int RPI = 64 / LPR;
+    __shared__ int32_t s_list[4][KM_SEG];
+    const int h = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int piece = blockIdx.x * 4 + wave;
+    if (piece >= n_pieces[h]) return;
+    const int4 desc = pieces[(size_t)h * max_pieces + piece];
+    const int cl = desc.x, row0 = desc.y, nrows = desc.z;
+    const int sub = lane / LPR, part = lane % LPR;
+    const T *Xh = X + (size_t)h * N * D;
+    const int32_t *pm = perm + (size_t)h * N;
+    const int32_t *ot = other + (size_t)h * N;
+    int32_t *list = s_list[wave];
+    const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    int cnt = 0;
+    for (int r = 0; r < nrows; r += 64) {
+        const int rr = r + lane;
+        const int src = (rr < nrows) ? pm[row0 + rr] : 0;
+        const bool take = rr < nrows && ot[src] != cl;
+        const unsigned long long m = __ballot(take);
+        if (take) list[cnt + __popcll(m & lt_mask)] = src;
+        cnt += __popcll(m);
+    }
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int r = 0; r < cnt; r += RPI * KM_UB) {
+        uint4 v[KM_UB];
+        bool ok[KM_UB];
+#pragma unroll
+        for (int u = 0; u < KM_UB; ++u) {
+            const int rr = r + u * RPI + sub;
+            ok[u] = rr < cnt;
+            const int src = list[min(rr, cnt - 1)];
+            v[u] = reinterpret_cast<const uint4 *>(Xh + (size_t)src * D)[part];
+        }
+#pragma unroll
+        for (int u = 0; u < KM_UB; ++u) {
+            if (!ok[u]) continue;
+            const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            if (sizeof(T) == 2) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[2 * q] += __uint_as_float(w[q] << 16);
+                    acc[2 * q + 1] += __uint_as_float(w[q] & 0xFFFF0000u);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += __uint_as_float(w[q]);
+            }
+        }
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
+    if (sub == 0) {
+        float *out = psum + ((size_t)h * max_pieces + piece) * D + part * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+            *reinterpret_cast<float4 *>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+    }
+}
+
 __global__ void kmeans_zero_kernel(float *p, int n)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -417,9 +507,12 @@ __global__ void kmeans_zero_kernel(float *p, int n)
 struct KmeansWs {
     bf16_t *cb;
     float *cn;
-    int32_t *offsets, *perm, *first_piece, *n_pieces;
-    int4 *pieces;
-    float *psum, *best;
+    // two sets of the label-sorted order and its pieces: iteration t uses set t % 2, so the previous iteration's
+    // order is still there for the delta update
+    int32_t *offsets[2], *perm[2], *first_piece[2], *n_pieces[2];
+    int4 *pieces[2];
+    float *psum[2], *best, *csum;
+    int32_t *labels_prev;
     void *sort_ws;
     int max_pieces;
     size_t total;
@@ -432,12 +525,16 @@ static KmeansWs kmeans_carve(void *ws, int H, int N, int d, int C)
     Carver c(ws);
     k.cb = c.take<bf16_t>((size_t)H * C * d);
     k.cn = c.take<float>((size_t)H * C);
-    k.offsets = c.take<int32_t>((size_t)H * (C + 1));
-    k.perm = c.take<int32_t>((size_t)H * N);
-    k.first_piece = c.take<int32_t>((size_t)H * (C + 1));
-    k.n_pieces = c.take<int32_t>((size_t)H);
-    k.pieces = c.take<int4>((size_t)H * k.max_pieces);
-    k.psum = c.take<float>((size_t)H * k.max_pieces * d);
+    for (int s = 0; s < 2; ++s) {
+        k.offsets[s] = c.take<int32_t>((size_t)H * (C + 1));
+        k.perm[s] = c.take<int32_t>((size_t)H * N);
+        k.first_piece[s] = c.take<int32_t>((size_t)H * (C + 1));
+        k.n_pieces[s] = c.take<int32_t>((size_t)H);
+        k.pieces[s] = c.take<int4>((size_t)H * k.max_pieces);
+        k.psum[s] = c.take<float>((size_t)H * k.max_pieces * d);
+    }
+    k.csum = c.take<float>((size_t)H * C * d);
+    k.labels_prev = c.take<int32_t>((size_t)H * N);
     k.best = c.take<float>(C > KM_CMAX ? (size_t)H * N : 0);
     k.sort_ws = c.take<char>(permute_ws_bytes(H, N, C));
     k.total = c.used;
@@ -457,10 +554,19 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
     const KmeansWs k = kmeans_carve(ws, H, N, D, C);
     if (objective)
         hipLaunchKernelGGL(kmeans_zero_kernel, dim3(cdiv(H * iters, 256)), dim3(256), 0, st, objective, H * iters);
-    hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, init, centroids, k.psum,
-                       k.first_piece, k.offsets, k.max_pieces, C, D, k.cb, k.cn, (int32_t *)nullptr, 0);
+    hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, init, centroids, k.psum[0],
+                       k.first_piece[0], k.offsets[0], k.max_pieces, C, D, k.cb, k.cn, (int32_t *)nullptr, 0, k.csum,
+                       (const float *)nullptr, (const int32_t *)nullptr);
     for (int t = 0; t < iters; ++t) {
         float *obj = objective ? objective + t : nullptr;
+        // Update step: the first KM_FULL_FIRST iterations, and every KM_FULL_EVERY-th after that, sum every
+        // cluster afresh; the others only move the tokens whose label changed (a few per cent from the third
+        // iteration on) between the cluster sums, which reads a tenth of X.
+        const bool full = t < KM_FULL_FIRST || t % KM_FULL_EVERY == 0;
+        const int s = t & 1;
+        if (!full)
+            SVG2_HIP_CHECK(hipMemcpyAsync(k.labels_prev, labels, (size_t)H * N * sizeof(int32_t),
+                                          hipMemcpyDeviceToDevice, st));
         if (BF16) {
             const dim3 grid(cdiv(cdiv(N, KM_WG_TOKENS), KM_IB), H);
             const bf16_t *Xb = reinterpret_cast<const bf16_t *>(X);
@@ -480,15 +586,28 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
                                    C, labels, obj, iters);
         }
         // label-sorted order of the tokens, then the segmented sum over it
-        const int rc = permute_launch(labels, H, N, C, k.offsets, k.perm, nullptr, 0, nullptr, nullptr, 0, 0,
+        const int rc = permute_launch(labels, H, N, C, k.offsets[s], k.perm[s], nullptr, 0, nullptr, nullptr, 0, 0,
                                       k.sort_ws, st);
         if (rc != SVG2_OK) return rc;
-        hipLaunchKernelGGL(kmeans_pieces_kernel, dim3(H), dim3(256), 0, st, k.offsets, C, k.max_pieces, k.pieces,
-                           k.first_piece, k.n_pieces);
-        hipLaunchKernelGGL((kmeans_segsum_kernel<T, D>), dim3(cdiv(k.max_pieces, 4), H), dim3(256), 0, st, X, k.perm, N,
-                           k.max_pieces, k.pieces, k.n_pieces, k.psum);
-        hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, (const float *)nullptr,
-                           centroids, k.psum, k.first_piece, k.offsets, k.max_pieces, C, D, k.cb, k.cn, counts, 1);
+        hipLaunchKernelGGL(kmeans_pieces_kernel, dim3(H), dim3(256), 0, st, k.offsets[s], C, k.max_pieces, k.pieces[s],
+                           k.first_piece[s], k.n_pieces[s]);
+        const dim3 sgrid(cdiv(k.max_pieces, 4), H);
+        if (full) {
+            hipLaunchKernelGGL((kmeans_segsum_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[s], N, k.max_pieces,
+                               k.pieces[s], k.n_pieces[s], k.psum[s]);
+            hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, (const float *)nullptr,
+                               centroids, k.psum[s], k.first_piece[s], k.offsets[s], k.max_pieces, C, D, k.cb, k.cn,
+                               counts, 1, k.csum, (const float *)nullptr, (const int32_t *)nullptr);
+        } else {
+            // tokens that joined a cluster: new order, previous labels; tokens that left: previous order, new labels
+            hipLaunchKernelGGL((kmeans_segsum_delta_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[s],
+                               k.labels_prev, N, k.max_pieces, k.pieces[s], k.n_pieces[s], k.psum[s]);
+            hipLaunchKernelGGL((kmeans_segsum_delta_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[1 - s], labels, N,
+                               k.max_pieces, k.pieces[1 - s], k.n_pieces[1 - s], k.psum[1 - s]);
+            hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, (const float *)nullptr,
+                               centroids, k.psum[s], k.first_piece[s], k.offsets[s], k.max_pieces, C, D, k.cb, k.cn,
+                               counts, 2, k.csum, k.psum[1 - s], k.first_piece[1 - s]);
+        }
     }
     return SVG2_OK;
 }
