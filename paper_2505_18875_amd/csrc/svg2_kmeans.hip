@@ -564,9 +564,10 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
         // iteration on) between the cluster sums, which reads a tenth of X.
         const bool full = t < KM_FULL_FIRST || t % KM_FULL_EVERY == 0;
         const int s = t & 1;
-        if (!full)
-            SVG2_HIP_CHECK(hipMemcpyAsync(k.labels_prev, labels, (size_t)H * N * sizeof(int32_t),
-                                          hipMemcpyDeviceToDevice, st));
+        // the labels of iteration t go to the caller's buffer when iters - 1 - t is even, else to the scratch
+        // buffer: the last iteration lands in the caller's buffer and the previous labels are always the other one
+        int32_t *lab = ((iters - 1 - t) & 1) ? k.labels_prev : labels;
+        const int32_t *lab_prev = ((iters - 1 - t) & 1) ? labels : k.labels_prev;
         if (BF16) {
             const dim3 grid(cdiv(cdiv(N, KM_WG_TOKENS), KM_IB), H);
             const bf16_t *Xb = reinterpret_cast<const bf16_t *>(X);
@@ -574,19 +575,19 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
             auto kern = obj ? kmeans_assign_bf16_kernel<D, true> : kmeans_assign_bf16_kernel<D, false>;
             SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, grid, dim3(64 * KM_NW), lds, st, Xb, k.cb, k.cn, N, C, labels, k.best, obj, iters);
+            hipLaunchKernelGGL(kern, grid, dim3(64 * KM_NW), lds, st, Xb, k.cb, k.cn, N, C, lab, k.best, obj, iters);
         } else {
             const dim3 grid(cdiv(N, 128), H);
             const float *Xf = reinterpret_cast<const float *>(X);
             if (obj)
                 hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, true>), grid, dim3(128), 0, st, Xf, centroids, k.cn, N,
-                                   C, labels, obj, iters);
+                                   C, lab, obj, iters);
             else
                 hipLaunchKernelGGL((kmeans_assign_f32_kernel<D, false>), grid, dim3(128), 0, st, Xf, centroids, k.cn, N,
-                                   C, labels, obj, iters);
+                                   C, lab, obj, iters);
         }
         // label-sorted order of the tokens, then the segmented sum over it
-        const int rc = permute_launch(labels, H, N, C, k.offsets[s], k.perm[s], nullptr, 0, nullptr, nullptr, 0, 0,
+        const int rc = permute_launch(lab, H, N, C, k.offsets[s], k.perm[s], nullptr, 0, nullptr, nullptr, 0, 0,
                                       k.sort_ws, st);
         if (rc != SVG2_OK) return rc;
         hipLaunchKernelGGL(kmeans_pieces_kernel, dim3(H), dim3(256), 0, st, k.offsets[s], C, k.max_pieces, k.pieces[s],
@@ -601,8 +602,8 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
         } else {
             // tokens that joined a cluster: new order, previous labels; tokens that left: previous order, new labels
             hipLaunchKernelGGL((kmeans_segsum_delta_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[s],
-                               k.labels_prev, N, k.max_pieces, k.pieces[s], k.n_pieces[s], k.psum[s]);
-            hipLaunchKernelGGL((kmeans_segsum_delta_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[1 - s], labels, N,
+                               lab_prev, N, k.max_pieces, k.pieces[s], k.n_pieces[s], k.psum[s]);
+            hipLaunchKernelGGL((kmeans_segsum_delta_kernel<T, D>), sgrid, dim3(256), 0, st, X, k.perm[1 - s], lab, N,
                                k.max_pieces, k.pieces[1 - s], k.n_pieces[1 - s], k.psum[1 - s]);
             hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(C, H), dim3(D), 0, st, (const float *)nullptr,
                                centroids, k.psum[s], k.first_piece[s], k.offsets[s], k.max_pieces, C, D, k.cb, k.cn,

@@ -15,7 +15,7 @@
 
 namespace svg2 {
 
-static constexpr int PERM_CHUNK = 2048;     // tokens per chunk (one wavefront in scatter)
+static constexpr int PERM_CHUNK = 1024;     // tokens per chunk (one wavefront in scatter)
 
 __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__restrict__ labels, int N, int C,
                                                            int nchunks, int32_t *__restrict__ hist)
@@ -34,7 +34,10 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__rest
 }
 
 // One workgroup per head.  hist[h][k][c] becomes the first sorted row that
-// chunk k writes for cluster c.
+// chunk k writes for cluster c.  The loads of a cluster's column are issued SCAN_UB at a time before they are
+// used, so the kernel waits for a few round trips to memory instead of one per chunk.
+static constexpr int SCAN_UB = 16;
+
 __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t *__restrict__ hist, int N, int C, int nchunks,
                                                            int32_t *__restrict__ offsets)
 {
@@ -44,10 +47,12 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t *__restrict__
     int32_t *hh = hist + (size_t)h * nchunks * C;
     for (int c = tid; c < C; c += 256) {
         int run = 0;
-        for (int k = 0; k < nchunks; ++k) {
-            int v = hh[(size_t)k * C + c];
-            hh[(size_t)k * C + c] = run;
-            run += v;
+        for (int k0 = 0; k0 < nchunks; k0 += SCAN_UB) {
+            int v[SCAN_UB];
+#pragma unroll
+            for (int u = 0; u < SCAN_UB; ++u) v[u] = (k0 + u < nchunks) ? hh[(size_t)(k0 + u) * C + c] : 0;
+#pragma unroll
+            for (int u = 0; u < SCAN_UB; ++u) run += v[u];
         }
         s_tot[c] = run;
     }
@@ -69,9 +74,18 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(int32_t *__restrict__
     __syncthreads();
     int32_t *off = offsets + (size_t)h * (C + 1);
     for (int c = tid; c < C; c += 256) {
-        const int o = s_tot[c];
-        off[c] = o;
-        for (int k = 0; k < nchunks; ++k) hh[(size_t)k * C + c] += o;
+        int pos = s_tot[c];
+        off[c] = pos;
+        for (int k0 = 0; k0 < nchunks; k0 += SCAN_UB) {
+            int v[SCAN_UB];
+#pragma unroll
+            for (int u = 0; u < SCAN_UB; ++u) v[u] = (k0 + u < nchunks) ? hh[(size_t)(k0 + u) * C + c] : 0;
+#pragma unroll
+            for (int u = 0; u < SCAN_UB; ++u) {
+                if (k0 + u < nchunks) hh[(size_t)(k0 + u) * C + c] = pos;
+                pos += v[u];
+            }
+        }
     }
     if (tid == 0) off[C] = N;
 }
