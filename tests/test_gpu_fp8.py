@@ -268,3 +268,23 @@ def test_forward_fp8_wan_like_full_size(svg2, oracle):
     d = (res.O.float() - ref.O.float())
     rel = (d.pow(2).sum((1, 2)) / ref.O.float().pow(2).sum((1, 2))).sqrt()
     assert float(rel.max()) < 0.3
+
+
+@pytest.mark.parametrize("N", [1, 31, 40, 65, 129])
+def test_sparse_attn_fp8_very_short_sequences(svg2, oracle, N):
+    # fewer keys than one 64-key tile, one tile and a bit, a query tile and a bit: everything ragged
+    r = np.random.default_rng(50 + N)
+    d = 128
+    Q, K, V = (wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32)) for _ in range(3))
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, to_dev(Q[None], "bf16"), to_dev(K[None], "bf16"),
+                                                 to_dev(V[None], "bf16"))
+    one = to_dev(np.array([[0, N]], dtype=np.int32))
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, one, one, to_dev(np.array([[0, 1]], dtype=np.int32)),
+                                    to_dev(np.zeros((1, 1), dtype=np.int32)), None, None, want_lse=True)
+    torch.cuda.synchronize()
+    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
+    O_ref, lse_ref = oracle.dense_attention(dq[1], dk[1], dv[1], scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
+    O_ref = O_ref * float(dv[2])
+    O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    assert np.abs(O - O_ref).max() <= O_MAX_FRAC * np.abs(V).max() + 1e-2
+    assert np.abs(lse - lse_ref).max() <= LSE_MAX

@@ -379,6 +379,35 @@ def _check_forward(oracle, svg2, w, heads, sample_rows=None):
     assert low_margin <= max(2, len(heads) * w.Cq // 20)
 
 
+def test_attention_many_heads_work_order_fallback(svg2, oracle):
+    # 65,535 heads (the largest H) of a very short sequence: with H * C_q above 2^20 the work items keep their
+    # head-major order instead of being sorted longest first; three heads are checked against the oracle
+    H, N, d, Cq, Ck = 65535, 32, 64, 17, 4
+    r = np.random.default_rng(99)
+    lq = np.sort(r.integers(0, Cq, size=N)).astype(np.int32)
+    lk = np.sort(r.integers(0, Ck, size=N)).astype(np.int32)
+    pq, pk = oracle.permute(lq, Cq), oracle.permute(lk, Ck)
+    sel = [np.sort(r.choice(Ck, size=int(r.integers(1, Ck + 1)), replace=False)) for _ in range(Cq)]
+    row_ptr = np.concatenate([[0], np.cumsum([len(x) for x in sel])]).astype(np.int32)
+    col = np.zeros(Cq * Ck, dtype=np.int32)
+    cat = np.concatenate(sel).astype(np.int32)
+    col[: cat.size] = cat
+    g = torch.Generator(device="cuda").manual_seed(5)
+    Q, K, V = (torch.randn((H, N, d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+               for _ in range(3))
+    rep = lambda a: to_dev(np.ascontiguousarray(np.broadcast_to(a[None], (H,) + a.shape)))  # noqa: E731
+    res = svg2.svg2_sparse_attn(Q, K, V, rep(pq.offsets), rep(pk.offsets), rep(row_ptr), rep(col), rep(pq.perm),
+                                want_lse=True)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(res.O.float()).all())
+    for h in (0, 31000, H - 1):
+        q, k, v = to_np(Q[h]), to_np(K[h]), to_np(V[h])
+        O_ref, lse_ref = oracle.sparse_attention(q, k, v, pq.offsets, pk.offsets, row_ptr, cat, perm_q=pq.perm)
+        err = np.abs(to_np(res.O[h]) - O_ref)
+        assert err.max() <= 2e-2 and err.mean() <= 1e-3, (h, err.max(), err.mean())
+        np.testing.assert_allclose(to_np(res.lse[h]), lse_ref, rtol=1e-3, atol=2e-3)
+
+
 def test_forward_tiny(svg2, oracle):
     _check_forward(oracle, svg2, wl.WORKLOADS["tiny"], [0])
 
