@@ -184,8 +184,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     const float *__restrict__ scale_q, const float *__restrict__ scale_k, const float *__restrict__ scale_v, int H,
     int N, int Cq, int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
-    const int32_t *__restrict__ order, int max_tiles, const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2_base,
-    int group, bf16_t *__restrict__ O, float *__restrict__ lse)
+    const int32_t *__restrict__ order, int max_tiles, const int2 *__restrict__ runs,
+    const int32_t *__restrict__ row_keys, float scale_log2_base, int group, bf16_t *__restrict__ O,
+    float *__restrict__ lse)
 {
     static_assert(D == 128, "row = 128 bytes: the swizzles below are written for that");
     constexpr int KU = D / 64;                 // matrix instructions per score block (64 values of d each)
@@ -358,14 +359,14 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     // ---- schedule.  Scores and probabilities are handled in blocks of 32 keys (two per tile), the second
     // product once per 64-key tile (its contraction index is the whole tile).  Per tile t, with s0 = scores of
     // its block 0 already there and the reference level m decided for them:
-    //   A:  s1 = K_{t,1} Q^T          (2 matrix instructions)  ||  pw0 = exp2(s0 - m), LDS reads of V_t^T and K_{t+1,0}
-    //   B:  maximum of s1, decision about m.  If m moved (rare): pw0 is recomputed under the new m and
-    //       the accumulators are rescaled, so that both halves of the tile share one level.
-    //   C:  s0 = K_{t+1,0} Q^T        (2)                      ||  pw1 = exp2(s1 - m), LDS reads of V_t^T and K_{t+1,1}
-    //   D:  O^T += V_t^T P^T, l += 1^T P^T   (4 + 1)           ||  maximum of the new s0, decision about m; the
-    //       accumulators are rescaled after the five instructions if m moved.
-    // Accumulator i of a score block is key 8 (i/4) + 4 half + i%4 of the block; word e of pw holds accumulators
-    // 4 e .. 4 e + 3; the B operand of the second product is pw0[0..3], pw1[0..3].
+    //   A:  s1 = K_{t,1} Q^T          (2 matrix instructions)  ||  pw[0..3] = exp2(s0 - m), LDS reads of V_t^T, K_{t+1,0}
+    //   B:  maximum of s1, decision about m.  If m moved (rare), pw[0..3] is recomputed under the new m, so that
+    //       both halves of the tile share one level.
+    //   C:  s0 = K_{t+1,0} Q^T        (2)                      ||  pw[4..7] = exp2(s1 - m), LDS reads of V_t^T, K_{t+1,1}
+    //   D:  accumulators brought to the level m if it moved since the last tile (rare);
+    //       O^T += V_t^T P^T (4), l += 1^T P^T (1, last)       ||  maximum of the new s0, decision about m
+    // Accumulator i of a score block is key 8 (i/4) + 4 half + i%4 of the block; word e of a block's probabilities
+    // holds accumulators 4 e .. 4 e + 3; the B operand of the second product is pw[0..7].
 #define ATT_FENCE __builtin_amdgcn_sched_barrier(0);
 #define ATT_PIN(X) asm volatile("" : "+v"(X));
     constexpr int NOPS = 40;                    // vector operations of one block's probabilities
@@ -378,7 +379,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     i32x8 ka[KU], va[DVB];                      // K operands of the next score block, V^T operands of this tile
     float m_acc = 0.f, t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
     for (int i = 0; i < 8; ++i) pw[i] = 0;
-    f32x16 lt = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // row sums of the tile just accumulated
+    f32x16 lt;                                  // row sums of the tile just accumulated (every element the same)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lt[i] = 0.f;
     bool any_upd = false;
 
     auto exp_op = [&](const f32x16 &S, auto w0_tag, int op) {
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         else if (k == 5) { t1 = __builtin_amdgcn_exp2f(t1); ATT_PIN(t1) }
         else if (k == 6) { t2 = __builtin_amdgcn_exp2f(t2); ATT_PIN(t2) }
         else if (k == 7) { t3 = __builtin_amdgcn_exp2f(t3); ATT_PIN(t3) }
-        else if (k == 8) { pw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, pw[w], false); ATT_PIN(pw[w]) }   // both halves get written
+        else if (k == 8) { pw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(t0, t1, pw[w], false); ATT_PIN(pw[w]) }
         else { pw[w] = __builtin_amdgcn_cvt_pk_fp8_f32(t2, t3, pw[w], true); ATT_PIN(pw[w]) }
     };
     auto mask_block = [&](f32x16 &S, int base, int rem) {
