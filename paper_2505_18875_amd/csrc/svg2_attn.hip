@@ -421,7 +421,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     f32x16 s0, s1;                              // scores of block 0 / block 1 of a tile
     unsigned pw0[8], pw1[8];                    // probabilities of block 0 / block 1, two bf16 per word
     bf16x8 ka[KS], va[NPV];                     // K operands of the next score block, V^T operands of this one
-    float psum = 0.f, alpha = 1.f, t0 = 0.f, t1 = 0.f;
+    float psum = 0.f, m_acc = 0.f, t0 = 0.f, t1 = 0.f;    // m_acc: the maximum the accumulators are expressed under
     bool any_upd = false;
 
     // operation `op` (0..47) of the probabilities of one block: S -> pw
@@ -444,11 +444,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         const float mx_s = max_xor32(mx) * scale_log2;
         const bool upd = mx_s > m_run + 8.0f;
         any_upd = __any(upd);
-        const float m_new = upd ? mx_s : m_run;
-        alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        m_run = upd ? mx_s : m_run;
         ATT_PIN(m_run)
-        ATT_PIN(alpha)
         psum = 0.f;
     };
     // K operands of a score block: KBYTE = byte offset of the block's first row in LDS
@@ -526,7 +523,9 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
             }
             ATT_FENCE
         }
-        if (DO_MAX && any_upd) {
+        if (DO_MAX && any_upd) {            // rare: the factor is only formed here
+            const float alpha = __builtin_amdgcn_exp2f(m_acc - m_run);
+            m_acc = m_run;
             l_run *= alpha;
 #pragma unroll
             for (int b = 0; b < DVB; ++b)
@@ -553,6 +552,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #pragma unroll
         for (int i = 3; i < 16; ++i) mx = fmaxf(mx, s0[i]);
         decide(mx);                             // key 0 exists, so the maximum is finite; nothing to rescale yet
+        m_acc = m_run;
 #pragma unroll
         for (int op = 0; op < OPS_B; ++op) exp_op(s0, pw0, op);
     }
