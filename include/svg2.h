@@ -17,6 +17,10 @@
  *     library allocates no device memory: scratch comes in through
  *     (ws, ws_bytes), whose required size the matching *_workspace_size
  *     function returns (0 is never returned; ws must be 256-byte aligned).
+ *     A call enqueues kernel launches only (no memset or copy commands, no
+ *     read-back of device values, launch sizes depend on the arguments
+ *     alone), so it may be recorded into a HIP graph and replayed; stale
+ *     workspace contents never matter.
  *   - Return value: SVG2_OK or an error code.  On any error nothing has been
  *     launched and svg2_last_error() (thread-local, HOST string) says why.
  *   - dtype is SVG2_F32 or SVG2_BF16 (storage type of Q, K, V, O); d is 64 or
