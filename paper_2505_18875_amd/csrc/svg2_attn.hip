@@ -310,8 +310,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     // rows then go from global memory straight into LDS (no staging registers): load
     // instruction (wave, p) fills LDS rows (NW p + wave) * RPI .. + RPI of the tile, lane l
     // the chunk position l % CPR of row l / CPR, so it fetches the global chunk that the
-    // swizzle puts there.  K tiles are fetched three tiles ahead of their use and V tiles
-    // two tiles ahead (see the schedule below), so the byte offsets of a tile's rows are
+    // swizzle puts there.  K tiles are fetched two tiles ahead of their use and V tiles
+    // one tile ahead (see the schedule below), so the byte offsets of a tile's rows are
     // kept in registers from its K fetch to its V fetch.
     const char *Kb = reinterpret_cast<const char *>(Kh);
     const char *Vb = reinterpret_cast<const char *>(Vh);
@@ -327,16 +327,41 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
         int row_ = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
-        if (perm_k) row_ = pkh[row_];           /* gather-free: sorted row -> token */     \
+        if (perm_k) {                           /* gather-free: sorted row -> token */     \
+            row_ = pkh[row_];                                                              \
+            asm volatile("" : "+v"(row_));      /* the wait for this load stays inside the branch */ \
+        }                                                                                  \
         s_rows[((KT) & 1) * ATT_BN + lane] = row_ * RB;     /* byte offset of the row */   \
+    }
+// second and third step of the look-up of a tile's rows (first step: lk_rs_ = s_run[cur], lk_nb_ = start of the next run)
+#define ATT_LOOKUP_FINISH(KT)                                                              \
+    {                                                                                      \
+        const int kk = (KT) * ATT_BN + lane;                                               \
+        if (kk < L) {                                                                      \
+            while (kk >= lk_nb_) {                                                         \
+                ++cur;                                                                     \
+                lk_rs_ = s_run[cur];                                                       \
+                lk_nb_ = s_run[cur + 1].y;                                                 \
+            }                                                                              \
+            lk_row_ = lk_rs_.x + kk - lk_rs_.y;                                            \
+        }                                                                                  \
+        if (perm_k) lk_row_ = pkh[lk_row_];     /* gather-free: sorted row -> token */     \
+    }
+#define ATT_LOOKUP_STORE(KT)                                                               \
+    {                                                                                      \
+        asm volatile("" : "+v"(lk_row_));       /* the value is first touched here, so the wait for it comes here */ \
+        s_rows[((KT) & 1) * ATT_BN + lane] = lk_row_ * RB;                                 \
     }
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
         OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
 #define ATT_FETCH(OFF, SRC, LOFF, DST)                                                     \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(SRC + (OFF[p_] + LOFF)), \
-                                         (__attribute__((address_space(3))) void *)(DST + ((NW * p_ + wave) * RPI) * RB), 16, 0, 0);
+        load_to_lds_16(SRC, OFF[p_] + LOFF, DST + ((NW * p_ + wave) * RPI) * RB);
+
+// one load instruction (pass P) of a tile: DSTB = byte offset of the tile's buffer in LDS
+#define ATT_FETCH1(P, OFF, SRC, LOFF, DSTB)                                                \
+    load_to_lds_16(SRC, OFF[P] + LOFF, s_raw + (DSTB) + ((NW * (P) + wave) * RPI) * RB);
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
     unsigned off_nx[NPASS];                     // row offsets of the tile whose V is fetched next
@@ -406,9 +431,15 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     // old maximum.  Accumulator i of a block is key 8 (i/4) + 4 half + i%4.
     //
     // Tile t lives in K buffer t % 2 and V buffer t % 2.  One barrier per tile: at the top of
-    // tile t every wavefront has finished tile t - 1 and all fetches issued a tile ago have
-    // landed; then V_{t+1} and K_{t+2} are requested (K is read one and a half blocks ahead
-    // of V, so it is fetched a tile earlier).
+    // tile t every wavefront has finished tile t - 1 and all fetches issued during tile t - 1
+    // have landed.  V_{t+1} and K_{t+2} are requested during tile t (K is read one and a half
+    // blocks ahead of V, so it is fetched a tile earlier): the V loads one by one after every
+    // other matrix instruction of the first phase A, the K loads likewise in the first phase B.
+    // Issued in one burst at the top of the tile, the load instructions of all wavefronts of a
+    // CU queue up behind each other (a CU accepts one 1 KB load per ~17 cycles) while no matrix
+    // instruction is in flight.  The rows of tile t + 3 are looked up by one wavefront in three
+    // steps between the phases (request the run, resolve it, park the row offsets in s_rows), so
+    // that neither the LDS latency nor the latency of the gathered index is waited for.
 #define ATT_FENCE __builtin_amdgcn_sched_barrier(0);
 // An empty volatile asm that "modifies" a value: the value has to exist at this point of the
 // program, so optimisation passes that work above the instruction scheduler cannot sink the
@@ -464,8 +495,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         __builtin_memcpy(reinterpret_cast<char *>(&va[idx]) + 8, &hi, 8);
     };
     // phase A: Sacc = K Q^T from ka[] (if DO_S)  ||  operations 16..47 of pw = exp2(Sexp - m), V^T operands from VBYTE
-    auto phase_a = [&](auto do_s_tag, auto vbyte_tag, f32x16 &Sacc, const f32x16 &Sexp, unsigned *pw) {
+    auto phase_a = [&](auto do_s_tag, auto vbyte_tag, auto vfetch_tag, f32x16 &Sacc, const f32x16 &Sexp, unsigned *pw) {
         constexpr bool DO_S = decltype(do_s_tag)::value;
+        constexpr int VFETCH = decltype(vfetch_tag)::value;     // >= 0: LDS byte offset of the V buffer to fill
+        constexpr int KPF = KS / NPASS;                         // k-steps per load instruction
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             if (DO_S) {
@@ -482,16 +515,22 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #pragma unroll
             for (int op = OPS_B + ((NOPS - OPS_B) * s) / KS; op < OPS_B + ((NOPS - OPS_B) * (s + 1)) / KS; ++op)
                 exp_op(Sexp, pw, op);
+            if constexpr (VFETCH >= 0) {
+                if (s % KPF == KPF - 1) { ATT_FETCH1(s / KPF, off_nx, Vb, ld_voff, VFETCH) }
+            }
             ATT_FENCE
         }
         l_run += psum;
     };
     // phase B: O^T += V^T P^T from va[] and pr[]  ||  maximum of Snext and the decision, then operations
     // 0..15 of pn = exp2(Snext - m) (if DO_MAX); K operands of the block after Snext from KBYTE (if DO_K)
-    auto phase_b = [&](auto do_max_tag, auto do_k_tag, auto kbyte_tag, const unsigned *pr, const f32x16 &Snext,
-                       unsigned *pn) {
+    auto phase_b = [&](auto do_max_tag, auto do_k_tag, auto kbyte_tag, auto kfetch_tag, auto slot_tag, bool do_kfetch,
+                       const unsigned *pr, const f32x16 &Snext, unsigned *pn) {
         constexpr bool DO_MAX = decltype(do_max_tag)::value;
         constexpr bool DO_K = decltype(do_k_tag)::value;
+        constexpr int KFETCH = decltype(kfetch_tag)::value;     // >= 0: LDS byte offset of the K buffer to fill
+        constexpr int SLOT = decltype(slot_tag)::value;         // which half of s_rows holds that tile's rows
+        constexpr int KF0 = NPV / 4;                            // first matrix instruction followed by a load
         constexpr int HB = NPV / 2;
         float mx = -INFINITY;
 #pragma unroll
@@ -520,6 +559,16 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #pragma unroll
                 for (int op = (OPS_B * (idx - HB)) / HB; op < (OPS_B * (idx - HB + 1)) / HB; ++op)
                     exp_op(Snext, pn, op);
+            }
+            if constexpr (KFETCH >= 0) {
+                if (do_kfetch) {
+                    if (idx == 0) {
+#pragma unroll
+                        for (int p_ = 0; p_ < NPASS; ++p_)
+                            off_nx[p_] = (unsigned)s_rows[SLOT * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
+                    }
+                    if (idx >= KF0 && idx < KF0 + NPASS) { ATT_FETCH1(idx - KF0, off_nx, Kb, ld_koff, KFETCH) }
+                }
             }
             ATT_FENCE
         }
@@ -565,28 +614,48 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         if (NSTG > 2 && kt + NSTG - 1 < ntile) __builtin_amdgcn_s_waitcnt(0x0F70 | ((NSTG - 2) * 2 * NPASS)); \
         else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
         __syncthreads();                                                                   \
-        if (HAS_NEXT) {                                                                    \
-            if (kt + NSTG - 1 < ntile) { ATT_FETCH(off_nx, Vb, ld_voff, sV + ((BUF + NSTG - 1) % NSTG) * TILE_B) } \
-            if (kt + NSTG < ntile) {                                                       \
-                ATT_OFFS(kt + NSTG, off_nx)                                                \
-                ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
-            }                                                                              \
-            if (kt + NSTG + 1 < ntile) { ATT_ROWS(kt + NSTG + 1) }                         \
-        }                                                                                  \
+        /* fetches of this tile: V of the next tile (it exists: HAS_NEXT) into the other V buffer, K of the  \
+           tile after it into this tile's K buffer; spread over the first two phases so that the load        \
+           instructions of the wavefronts of a CU do not queue up behind each other at the top of a tile */  \
+        constexpr int VF_ = HAS_NEXT ? NSTG * TILE_B + ((BUF + 1) % NSTG) * TILE_B : -1;   \
+        constexpr int KF_ = HAS_NEXT ? BUF * TILE_B : -1;                                  \
+        const bool do_kf_ = HAS_NEXT && kt + NSTG < ntile;                                 \
+        /* rows of tile kt + 3 (needed by the K fetch of the next tile): one wavefront looks them up, in   \
+           three steps between the phases so that the LDS and memory latencies are not waited for */     \
+        const bool lk_ = HAS_NEXT && kt + NSTG + 1 < ntile && wave == ((kt + NSTG + 1) & (NW - 1)); \
+        int2 lk_rs_ = make_int2(0, 0);                                                     \
+        int lk_nb_ = 0, lk_row_ = 0;                                                       \
+        if (lk_) { lk_rs_ = s_run[cur]; lk_nb_ = s_run[cur + 1].y; }                       \
         if (wave_active) {                                                                 \
             using HN = std::integral_constant<bool, HAS_NEXT>;                             \
             constexpr int KB_ = ((BUF + 1) % NSTG) * TILE_B, VB_ = NSTG * TILE_B + BUF * TILE_B; \
-            phase_a(T{}, std::integral_constant<int, VB_>{}, s1, s0, pw0);                 \
+            phase_a(T{}, std::integral_constant<int, VB_>{}, std::integral_constant<int, VF_>{}, s1, s0, pw0); \
             if (!HAS_NEXT) mask_block(s1, 32, L - kt * ATT_BN);                            \
-            phase_b(T{}, HN{}, std::integral_constant<int, KB_>{}, pw0, s1, pw1);          \
-            phase_a(HN{}, std::integral_constant<int, VB_ + 32 * RB>{}, s0, s1, pw1);      \
+            if (lk_) { ATT_LOOKUP_FINISH(kt + NSTG + 1) }                                  \
+            phase_b(T{}, HN{}, std::integral_constant<int, KB_>{}, std::integral_constant<int, KF_>{}, \
+                    std::integral_constant<int, BUF>{}, do_kf_, pw0, s1, pw1);             \
+            phase_a(HN{}, std::integral_constant<int, VB_ + 32 * RB>{}, std::integral_constant<int, -1>{}, s0, s1, pw1); \
             if (HAS_NEXT && kt + 2 == ntile && L - (kt + 1) * ATT_BN < 32)                 \
                 mask_block(s0, 0, L - (kt + 1) * ATT_BN);                                  \
-            phase_b(HN{}, HN{}, std::integral_constant<int, KB_ + 32 * RB>{}, pw1, s0, pw0); \
+            phase_b(HN{}, HN{}, std::integral_constant<int, KB_ + 32 * RB>{}, std::integral_constant<int, -1>{}, \
+                    std::integral_constant<int, 0>{}, false, pw1, s0, pw0);                \
+            /* stored at the end of the tile: the wait for the gathered index (all loads: the compiler  \
+               does not know which are outstanding) then falls together with the one at the top */      \
+            if (lk_) { ATT_LOOKUP_STORE(kt + NSTG + 1) }                                   \
+        } else if (HAS_NEXT) {      /* a wavefront without query rows still loads its share of the tiles */ \
+            ATT_FETCH(off_nx, Vb, ld_voff, sV + ((BUF + NSTG - 1) % NSTG) * TILE_B)        \
+            if (do_kf_) {                                                                  \
+                ATT_OFFS(kt + NSTG, off_nx)                                                \
+                ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
+            }                                                                              \
+            if (lk_) {                                                                     \
+                ATT_LOOKUP_FINISH(kt + NSTG + 1)                                           \
+                ATT_LOOKUP_STORE(kt + NSTG + 1)                                            \
+            }                                                                              \
         }                                                                                  \
         ++kt;                                                                              \
     }
-    static_assert(NSTG == 2 || NSTG == 3, "the tile loop is unrolled by the number of buffers");
+    static_assert(NSTG == 2, "the fetch schedule below is written for two buffers");
     int kt = 0;
     while (kt < ntile - 1) {                    // every tile but the last
         ATT_TILE(0, true)
@@ -608,7 +677,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #undef ATT_PIN
 #undef ATT_ROWS
 #undef ATT_OFFS
+#undef ATT_LOOKUP_FINISH
+#undef ATT_LOOKUP_STORE
 #undef ATT_FETCH
+#undef ATT_FETCH1
 
     // ---- epilogue: normalise, store at the original row
     {

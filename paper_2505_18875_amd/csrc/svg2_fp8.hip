@@ -302,8 +302,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
 #define ATT_FETCH(OFF, SRC, LOFF, DST)                                                     \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(SRC + (OFF[p_] + LOFF)), \
-                                         (__attribute__((address_space(3))) void *)(DST + ((NW * p_ + wave) * RPI) * RB), 16, 0, 0);
+        load_to_lds_16(SRC, OFF[p_] + LOFF, DST + ((NW * p_ + wave) * RPI) * RB);
 
     const int ntile = (L + ATT_BN - 1) / ATT_BN;
     unsigned off_nx[NPASS];
