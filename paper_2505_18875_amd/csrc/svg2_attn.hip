@@ -36,7 +36,7 @@ namespace svg2 {
 // Launch shape of the bf16 kernel.  Measured on the Wan-like layer (8-head probe, ms sparse / dense):
 // 4 wavefronts, 2 buffers, 2 workgroups per CU 7.76 / 24.5;  8 wavefronts, 3 buffers, 1 workgroup per CU
 // (half the L2 -> LDS traffic, but 8 wavefronts behind one barrier) 8.17 / 25.7.
-static constexpr int ATT_NSTG = 2;         // K and V tile buffers in LDS (each): 2 or 3
+static constexpr int ATT_NSTG = 2;         // K and V tile buffers in LDS (each); the schedule is written for two
 static constexpr int ATT_OPS_B = 0;        // vector operations of a block's probabilities done early (see phase B)
 
 // ---------------------------------------------------------------- plan
@@ -376,19 +376,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     if (ntile > 1) {
         ATT_OFFS(1, off_nx)
         ATT_FETCH(off_nx, Kb, ld_koff, sK + TILE_B)
-        if (NSTG > 2) { ATT_FETCH(off_nx, Vb, ld_voff, sV + TILE_B) }
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
-    if (NSTG > 2) {
-        if (ntile > 3) { ATT_ROWS(3) }
-        __syncthreads();
-        if (ntile > 2) {
-            ATT_OFFS(2, off_nx)
-            ATT_FETCH(off_nx, Kb, ld_koff, sK + 2 * TILE_B)
-        }
-    }
-    // off_nx stays live: it holds the rows of tile NSTG - 1, whose V is requested at the top of tile 0
+    // off_nx stays live: it holds the rows of tile 1, whose V is requested during tile 0
     // per-lane LDS read offsets (bytes, buffer 0): K operand of k-step s, V^T operand of column block b
     int koff[KS], voff[DVB];
     {
@@ -607,12 +598,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     }
 
     // One tile: tile kt sits in K / V buffer BUF = kt % NSTG.  HAS_NEXT: tile kt + 1 exists.
-    // At the top, the fetches issued NSTG - 1 tiles ago (V of this tile, K of the next) must
-    // have landed; younger ones may still be in flight.
+    // At the top, the fetches issued during the tile before (V of this tile, K of the next) must
+    // have landed.
 #define ATT_TILE(BUF, HAS_NEXT)                                                            \
     {                                                                                      \
-        if (NSTG > 2 && kt + NSTG - 1 < ntile) __builtin_amdgcn_s_waitcnt(0x0F70 | ((NSTG - 2) * 2 * NPASS)); \
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
+        __builtin_amdgcn_s_waitcnt(0x0F70);     /* vmcnt(0) */                             \
         __syncthreads();                                                                   \
         /* fetches of this tile: V of the next tile (it exists: HAS_NEXT) into the other V buffer, K of the  \
            tile after it into this tile's K buffer; spread over the first two phases so that the load        \
@@ -661,16 +651,10 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         ATT_TILE(0, true)
         if (kt >= ntile - 1) break;
         ATT_TILE(1, true)
-        if constexpr (NSTG == 3) {
-            if (kt >= ntile - 1) break;
-            ATT_TILE((NSTG - 1), true)
-        }
     }
     if (ntile > 0) {                            // the last tile: nothing follows it, maybe ragged
-        const int bl = kt % NSTG;
-        if (bl == 0) ATT_TILE(0, false)
-        else if (bl == 1) ATT_TILE(1, false)
-        else if constexpr (NSTG == 3) ATT_TILE((NSTG - 1), false)
+        if (kt % NSTG == 0) ATT_TILE(0, false)
+        else ATT_TILE(1, false)
     }
 #undef ATT_TILE
 #undef ATT_FENCE
