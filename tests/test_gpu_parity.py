@@ -304,6 +304,28 @@ def test_attention_random_blocks_with_ragged_and_empty_clusters(svg2, oracle, dt
         assert rows.size and np.all(O[rows] == 0.0)
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_attention_tile_loop_edges_random_small_shapes(svg2, oracle, d):
+    """The matrix-core kernel's tile loop has a schedule with look-ahead (K two tiles ahead, V one, the row look-up
+    three): walk it through every length from no key tile to a dozen, with query tiles that fill one to four
+    wavefronts, key clusters shorter than a tile, and both row sources (permuted copies, gather-free)."""
+    r = np.random.default_rng(9000 + d)
+    for case in range(40):
+        N = int(r.choice([1, 2, 31, 33, 63, 64, 65, 127, 129, 200, 257, 400, 650, 770]))
+        Cq = int(r.integers(1, min(N, 5) + 1))
+        Ck = int(r.integers(1, min(N, 12) + 1))
+        Q, K, V = (wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32)) for _ in range(3))
+        lq = r.integers(0, Cq, size=N).astype(np.int32)
+        lk = r.integers(0, Ck, size=N).astype(np.int32)
+        if case % 3 == 0:
+            lk[: N // 2] = 0                                # one long run, the others short
+        sel = [np.sort(r.choice(Ck, size=int(r.integers(0, Ck + 1)), replace=False)) for _ in range(Cq)]
+        # With a handful of keys per row the outputs are O(1), not O(1 / sqrt(keys)) as on the workloads the
+        # mean-abs bar of 1e-3 was set for: the bf16 rounding of the stored output alone (2^-9 relative) is up to
+        # 2e-3 per element, so the mean bar is widened to 4e-3 here; the max bar stays.
+        _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", tol=(2e-2, 4e-3))
+
+
 def test_attention_dense_special_case_matches_dense_oracle(svg2, oracle):
     r = np.random.default_rng(5)
     N, d = 1000, 128
