@@ -37,6 +37,7 @@ namespace svg2 {
 // 4 wavefronts, 2 buffers, 2 workgroups per CU 7.76 / 24.5;  8 wavefronts, 3 buffers, 1 workgroup per CU
 // (half the L2 -> LDS traffic, but 8 wavefronts behind one barrier) 8.17 / 25.7.
 static constexpr int ATT_NSTG = 2;         // K and V tile buffers in LDS (each); the schedule is written for two
+static constexpr int ATT_RUN_LDS = 1920;     // runs of a work item kept in LDS (15 KB: two workgroups of 80 KB still fit a CU)
 static constexpr int ATT_OPS_B = 0;        // vector operations of a block's probabilities done early (see phase B)
 
 // ---------------------------------------------------------------- plan
@@ -48,7 +49,8 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
                                                         int max_tiles, int4 *__restrict__ tiles,
                                                         int32_t *__restrict__ n_tiles, int2 *__restrict__ runs,
                                                         int32_t *__restrict__ row_keys,
-                                                        int32_t *__restrict__ cl_first)
+                                                        int32_t *__restrict__ cl_first, int key_tiles,
+                                                        int32_t *__restrict__ tile_run)
 {
     __shared__ int32_t s_wave[4];
     __shared__ int32_t s_carry;
@@ -103,7 +105,13 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
                 const int v = __shfl_up(incl, o);
                 if (lane >= o) incl += v;
             }
-            if (idx < e1) rn[idx] = make_int2(start, carry + incl - len);
+            if (idx < e1) {
+                const int before = carry + incl - len;          // keys of the row in front of this run
+                rn[idx] = make_int2(start, before);
+                // the 64-key tiles whose first key lies in this run start their row look-up here
+                int32_t *tr = tile_run + ((size_t)h * Cq + i) * key_tiles;
+                for (int t = (before + ATT_BN - 1) / ATT_BN; t * ATT_BN < before + len && t < key_tiles; ++t) tr[t] = idx - e0;
+            }
             carry += __shfl(incl, 63);
         }
         if (lane == 0) row_keys[(size_t)h * Cq + i] = carry;
@@ -223,14 +231,16 @@ __device__ __forceinline__ bf16x8 pb_operand(const unsigned *pw, int k)
     return r;
 }
 
-template <int D>
+// RUN_CAP: the launch was sized for at most ATT_RUN_LDS runs in LDS (more than that many key clusters); a work item
+// with more runs then reads them from global memory.  Without it the table always fits and that path does not exist.
+template <int D, bool RUN_CAP>
 __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, int H, int N, int Cq,
     int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
     const int32_t *__restrict__ order, int max_tiles,
-    const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, float scale_log2, int group,
-    bf16_t *__restrict__ O, float *__restrict__ lse)
+    const int2 *__restrict__ runs, const int32_t *__restrict__ row_keys, const int32_t *__restrict__ tile_run,
+    int key_tiles, float scale_log2, int group, bf16_t *__restrict__ O, float *__restrict__ lse)
 {
     constexpr int KS = D / 16;                 // k-steps of QK^T
     constexpr int DVB = D / 32;                // 32-row blocks of O^T
@@ -277,8 +287,19 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const int nnz = row_ptr[(size_t)h * (Cq + 1) + ci + 1] - e0;
     const int L = row_keys[(size_t)h * Cq + ci];
     const int2 *rn = runs + (size_t)h * Cq * Ck + e0;
-    for (int e = tid; e < nnz; e += 64 * NW) s_run[e] = rn[e];
-    if (tid == 0) s_run[nnz] = make_int2(0, L);
+    const int32_t *trh = tile_run + ((size_t)h * Cq + ci) * key_tiles;      // run in which each key tile starts
+    // The run table of the work item (nnz entries + a closing one) is staged in LDS when it fits the share of LDS
+    // that still lets two workgroups run on a CU; a query cluster that selects more key clusters than that reads
+    // its runs from global memory (slow look-ups, same result).
+    const bool runs_in_lds = !RUN_CAP || nnz + 1 <= ATT_RUN_LDS;
+    if (runs_in_lds) {
+        for (int e = tid; e < nnz; e += 64 * NW) s_run[e] = rn[e];
+        if (tid == 0) s_run[nnz] = make_int2(0, L);
+    }
+    auto run_at = [&](int c) -> int2 {
+        if (!RUN_CAP || runs_in_lds) return s_run[c];
+        return c < nnz ? rn[c] : make_int2(0, L);
+    };
 
     const bf16_t *Qh = Q + (size_t)h * N * D;
     const bf16_t *Kh = K + (size_t)h * N * D;
@@ -316,7 +337,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     const char *Kb = reinterpret_cast<const char *>(Kh);
     const char *Vb = reinterpret_cast<const char *>(Vh);
     const int32_t *pkh = perm_k ? perm_k + (size_t)h * N : nullptr;
-    int cur = 0;
+    int cur = 0;                                // per-lane cursor into the run table, only moves forward
+    int lk_hint = -1;                           // run in which the tile looked up next starts (-1: not known)
     const int ld_row = lane / CPR;                                  // row inside the instruction's group
     const int ld_swz = ((wave * RPI + ld_row) / (256 / RB));
     const unsigned ld_koff = (unsigned)(((lane % CPR) ^ (ld_swz % CPR)) * 16);
@@ -326,7 +348,12 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
 #define ATT_ROWS(KT)                                                                       \
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
-        int row_ = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
+        int row_ = 0;                                                                      \
+        if (kk < L) {                                                                      \
+            while (kk >= run_at(cur + 1).y) ++cur;                                         \
+            const int2 rs_ = run_at(cur);                                                  \
+            row_ = rs_.x + kk - rs_.y;                                                     \
+        }                                                                                  \
         if (perm_k) {                           /* gather-free: sorted row -> token */     \
             row_ = pkh[row_];                                                              \
             asm volatile("" : "+v"(row_));      /* the wait for this load stays inside the branch */ \
@@ -340,8 +367,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         if (kk < L) {                                                                      \
             while (kk >= lk_nb_) {                                                         \
                 ++cur;                                                                     \
-                lk_rs_ = s_run[cur];                                                       \
-                lk_nb_ = s_run[cur + 1].y;                                                 \
+                lk_rs_ = run_at(cur);                                                      \
+                lk_nb_ = run_at(cur + 1).y;                                                \
             }                                                                              \
             lk_row_ = lk_rs_.x + kk - lk_rs_.y;                                            \
         }                                                                                  \
@@ -379,6 +406,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
+    if (ntile > 3 && 3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];      // tile 3 is looked up during tile 0
     // off_nx stays live: it holds the rows of tile 1, whose V is requested during tile 0
     // per-lane LDS read offsets (bytes, buffer 0): K operand of k-step s, V^T operand of column block b
     int koff[KS], voff[DVB];
@@ -615,7 +643,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
         const bool lk_ = HAS_NEXT && kt + NSTG + 1 < ntile && wave == ((kt + NSTG + 1) & (NW - 1)); \
         int2 lk_rs_ = make_int2(0, 0);                                                     \
         int lk_nb_ = 0, lk_row_ = 0;                                                       \
-        if (lk_) { lk_rs_ = s_run[cur]; lk_nb_ = s_run[cur + 1].y; }                       \
+        if (lk_) {                                                                         \
+            cur = max(cur, lk_hint);            /* start at the tile's first run, not where this lane was 4 tiles ago */ \
+            lk_rs_ = run_at(cur);                                                          \
+            lk_nb_ = run_at(cur + 1).y;                                                    \
+        }                                                                                  \
         if (wave_active) {                                                                 \
             using HN = std::integral_constant<bool, HAS_NEXT>;                             \
             constexpr int KB_ = ((BUF + 1) % NSTG) * TILE_B, VB_ = NSTG * TILE_B + BUF * TILE_B; \
@@ -642,6 +674,13 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_bf16_kernel(
                 ATT_LOOKUP_FINISH(kt + NSTG + 1)                                           \
                 ATT_LOOKUP_STORE(kt + NSTG + 1)                                            \
             }                                                                              \
+        }                                                                                  \
+        /* where the tile that the next tile looks up starts (from the plan, global memory): requested here, \
+           used behind the wait at the top of the next tile */                                              \
+        {                                                                                  \
+            const int tn_ = kt + NSTG + 2;                                                 \
+            lk_hint = -1;                                                                  \
+            if (HAS_NEXT && tn_ < ntile && tn_ < key_tiles && wave == (tn_ & (NW - 1))) lk_hint = trh[tn_]; \
         }                                                                                  \
         ++kt;                                                                              \
     }
@@ -790,25 +829,16 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(
 size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
 {
     (void)d;
-    const int max_tiles = cdiv(N, attn_bm(dtype)) + Cq;
-    Carver c(nullptr);
-    c.take<int4>((size_t)H * max_tiles);
-    c.take<int32_t>((size_t)H);
-    c.take<int32_t>((size_t)H + 1);
-    c.take<int2>((size_t)H * Cq * Ck);
-    c.take<int32_t>((size_t)H * Cq);
-    c.take<int32_t>((size_t)H * Cq);
-    c.take<int32_t>((size_t)H * max_tiles);
-    return c.used;
+    return attn_carve(nullptr, dtype, H, N, Cq, Ck).bytes;
 }
-
 
 int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
                      const int32_t *row_ptr, const int32_t *col_idx, void *ws, hipStream_t st)
 {
     const AttnWs a = attn_carve(ws, dtype, H, N, Cq, Ck);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(H), dim3(256), 0, st, offsets_q, offsets_k, row_ptr, col_idx, Cq, Ck,
-                       attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys, a.cl_first);
+                       attn_bm(dtype), a.max_tiles, a.tiles, a.n_tiles, a.runs, a.row_keys, a.cl_first, a.key_tiles,
+                       a.tile_run);
     hipLaunchKernelGGL(attn_tile_base_kernel, dim3(1), dim3(256), 0, st, a.n_tiles, H, a.tile_base);
     if (dtype == SVG2_BF16)                     // the fp32 kernel is launched on a (tile, head) grid and needs no list
         hipLaunchKernelGGL(attn_order_kernel, dim3(1), dim3(1024), 0, st, offsets_q, a.tile_base, a.row_keys,
@@ -838,20 +868,14 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
         const size_t lds = (size_t)2 * ATT_NSTG * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
-                           (size_t)(Ck + 1) * sizeof(int2);
-        if (d == 128) {
-            auto kern = attn_bf16_kernel<128>;
-            SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
-                               tiles, tile_base, a.order, max_tiles, runs, row_keys, scale_log2, group, o, lse);
-        } else {
-            auto kern = attn_bf16_kernel<64>;
-            SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k,
-                               tiles, tile_base, a.order, max_tiles, runs, row_keys, scale_log2, group, o, lse);
-        }
+                           (size_t)std::min(Ck + 1, ATT_RUN_LDS) * sizeof(int2);
+        const bool cap = Ck + 1 > ATT_RUN_LDS;
+        auto kern = d == 128 ? (cap ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
+                             : (cap ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
+        SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k, tiles,
+                           tile_base, a.order, max_tiles, runs, row_keys, a.tile_run, a.key_tiles, scale_log2, group, o, lse);
     } else {
         const float *q = static_cast<const float *>(Qp), *k = static_cast<const float *>(Kp),
                     *v = static_cast<const float *>(Vp);

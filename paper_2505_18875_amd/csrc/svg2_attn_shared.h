@@ -111,13 +111,17 @@ struct AttnWs {
     int32_t *row_keys;
     int32_t *cl_first;                  // [H][Cq] first tile (inside its head) of every query cluster
     int32_t *order;                     // [all tiles] work items, longest first
-    int max_tiles;
+    int32_t *tile_run;                  // [H][Cq][key_tiles] CSR entry (relative to the row's first) of the run that
+                                        // holds key 64 t of the row's virtual key sequence
+    int max_tiles, key_tiles;
+    size_t bytes;
 };
 
 inline AttnWs attn_carve(void *ws, int dtype, int H, int N, int Cq, int Ck)
 {
     AttnWs a;
     a.max_tiles = cdiv(N, attn_bm(dtype)) + Cq;
+    a.key_tiles = cdiv(N, ATT_BN) + 1;
     Carver c(ws);
     a.tiles = c.take<int4>((size_t)H * a.max_tiles);
     a.n_tiles = c.take<int32_t>((size_t)H);
@@ -126,6 +130,8 @@ inline AttnWs attn_carve(void *ws, int dtype, int H, int N, int Cq, int Ck)
     a.row_keys = c.take<int32_t>((size_t)H * Cq);
     a.cl_first = c.take<int32_t>((size_t)H * Cq);
     a.order = c.take<int32_t>((size_t)H * a.max_tiles);
+    a.tile_run = c.take<int32_t>((size_t)H * Cq * a.key_tiles);
+    a.bytes = c.used;
     return a;
 }
 

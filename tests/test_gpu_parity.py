@@ -326,6 +326,20 @@ def test_attention_tile_loop_edges_random_small_shapes(svg2, oracle, d):
         _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", tol=(2e-2, 4e-3))
 
 
+def test_attention_more_selected_key_clusters_than_the_run_table_in_lds_holds(svg2, oracle):
+    """The matrix-core kernel keeps the (first row, keys before) table of a query cluster's selected key clusters in LDS
+    up to 1919 entries and reads it from global memory beyond: one row of this case selects 2600 of 2700 key clusters
+    (most of them 1-2 keys long, so a 64-key tile crosses dozens of runs), one 1500, one 3."""
+    r = np.random.default_rng(77)
+    N, d, Cq, Ck = 4200, 128, 3, 2700
+    Q, K, V = (wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32)) for _ in range(3))
+    lq = r.integers(0, Cq, size=N).astype(np.int32)
+    lk = r.integers(0, Ck, size=N).astype(np.int32)
+    sel = [np.sort(r.choice(Ck, size=2600, replace=False)), np.sort(r.choice(Ck, size=1500, replace=False)),
+           np.array([5, 900, 2699], dtype=np.int64)]
+    _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", tol=(2e-2, 4e-3))
+
+
 def test_attention_dense_special_case_matches_dense_oracle(svg2, oracle):
     r = np.random.default_rng(5)
     N, d = 1000, 128
