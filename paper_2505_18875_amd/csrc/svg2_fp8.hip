@@ -185,8 +185,8 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     int N, int Cq, int Ck, const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ perm_q,
     const int32_t *__restrict__ perm_k, const int4 *__restrict__ tiles, const int32_t *__restrict__ tile_base,
     const int32_t *__restrict__ order, int max_tiles, const int2 *__restrict__ runs,
-    const int32_t *__restrict__ row_keys, float scale_log2_base, int group, bf16_t *__restrict__ O,
-    float *__restrict__ lse)
+    const int32_t *__restrict__ row_keys, const int32_t *__restrict__ tile_run, int key_tiles, float scale_log2_base,
+    int group, bf16_t *__restrict__ O, float *__restrict__ lse)
 {
     static_assert(D == 128, "row = 128 bytes: the swizzles below are written for that");
     constexpr int KU = D / 64;                 // matrix instructions per score block (64 values of d each)
@@ -229,6 +229,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     const int nnz = row_ptr[(size_t)h * (Cq + 1) + ci + 1] - e0;
     const int L = row_keys[(size_t)h * Cq + ci];
     const int2 *rn = runs + (size_t)h * Cq * Ck + e0;
+    const int32_t *trh = tile_run + ((size_t)h * Cq + ci) * key_tiles;      // run in which each key tile starts
     for (int e = tid; e < nnz; e += 64 * NW) s_run[e] = rn[e];
     if (tid == 0) s_run[nnz] = make_int2(0, L);
 
@@ -265,6 +266,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     // ---- loader: as in the bf16 kernel (rows looked up by one wavefront, global -> LDS directly)
     const int32_t *pkh = perm_k ? perm_k + (size_t)h * N : nullptr;
     int cur = 0, row_pend = 0;
+    int lk_hint = -1;                           // run in which the tile looked up next starts (-1: not known)
     const int ld_row = lane / CPR;
     const int ld_r = wave * RPI + ld_row;       // tile row modulo 32 (load pass p adds 32 p)
     const unsigned ld_koff = (unsigned)(((lane % CPR) ^ ((ld_r >> 1) & 7)) * 16);
@@ -286,6 +288,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 #define ATT_ROWS_ISSUE(KT)                                                                 \
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
+        cur = max(cur, lk_hint);                /* start at the tile's first run (from the plan) */ \
         row_pend = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
         if (perm_k) {                                                                      \
             const int32_t *src_ = pkh + row_pend;                                          \
@@ -321,6 +324,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
+    if (F8_NSTG == 2 && ntile > 3 && 3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];    // tile 3 is looked up during tile 0
     if (NSTG > 2) {
         if (ntile > 3) { ATT_ROWS(3) }
         __syncthreads();
@@ -567,6 +571,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
             phase_pv(HN{}, VB{}, s0);                                                      \
         }                                                                                  \
         if (HAS_NEXT && kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }          \
+        {       /* where the tile that the next tile looks up starts: requested here, used behind the wait at the top */ \
+            const int tn_ = kt + NSTG + 2;                                                 \
+            lk_hint = -1;                                                                  \
+            if (HAS_NEXT && tn_ < ntile && tn_ < key_tiles && wave == (tn_ & (NW - 1))) lk_hint = trh[tn_]; \
+        }                                                                                  \
         ++kt;                                                                              \
     }
     static_assert(NSTG == 2 || NSTG == 3, "the tile loop is unrolled by the number of buffers");
@@ -639,7 +648,7 @@ int attn_fp8_main_launch(const void *Q8, const void *K8, const void *V8, const f
     hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, static_cast<const uint8_t *>(Q8),
                        static_cast<const uint8_t *>(K8), static_cast<const uint8_t *>(V8), scale_q, scale_k, scale_v, H,
                        N, Cq, Ck, row_ptr, perm_q, perm_k, a.tiles, a.tile_base, a.order, a.max_tiles, a.runs, a.row_keys,
-                       scale_log2, group, static_cast<bf16_t *>(O), lse);
+                       a.tile_run, a.key_tiles, scale_log2, group, static_cast<bf16_t *>(O), lse);
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
 }
