@@ -8,8 +8,11 @@ figures; every number comes from the library's kernels through the C ABI):
              previous step's centroids                                 (Section 4.3 / 5.3, Fig. 5a)
   fp8        output error and speed of the E4M3 attention path against the bf16 path, both measured against
              the fp32 kernel on the same selection                     (Table 1, "+ FP8" rows)
+  sequence   a denoising sequence: 10 steps, Q and K drifting by 0.05 N(0,1) per step, k-means warm-started
+             from the previous step's centroids with 2 iterations, C_k in {500, 1000}, top-p from 0.5 to
+             0.99: per-step layer time, density and attention recall      (Section 4.3, centroid cache)
 
-Usage: python -m paper_2505_18875_amd.diagnostics {recall,clusters,seeding,fp8} [--workload wan_like] [--heads 8]
+Usage: python -m paper_2505_18875_amd.diagnostics {recall,clusters,seeding,fp8,sequence} [--workload wan_like] [--heads 8]
 """
 from __future__ import annotations
 
@@ -212,9 +215,68 @@ def fp8(args):
         del ref, ob, o8
 
 
+def sequence(args):
+    import torch
+    import paper_2505_18875_amd as svg2
+    w = wl.WORKLOADS[args.workload]
+    heads = list(range(args.heads))
+    H, steps = len(heads), 10
+    Q, K, V, Qd0, Kd0, Vd = _inputs(w, heads)
+    flops = 4.0 * H * float(w.N) ** 2 * w.d
+    print("Denoising sequence: %s, heads 0..%d, %d steps; step 0 runs %d k-means iterations from the seeded centroids, every "
+          "later step drifts Q and K by 0.05 N(0,1) (drawn on the device, seeded) and runs 2 iterations from the previous "
+          "step's centroids.  Times are means over steps 1..%d of svg2_forward on these %d heads; recall is measured at the "
+          "last step (share of the true attention mass that the selected keys hold, mean over queries)."
+          % (w.name, args.heads - 1, steps, w.iters, steps - 1, H))
+    print("\n| C_k | top-p | density (steps 1..9) | step 0 ms | later steps ms | of which k-means | attention | TFLOP/s on selected | "
+          "recall at step 9 | labels changed by the 2nd warm iteration |\n|---|---|---|---|---|---|---|---|---|---|")
+    for Ck in (500, 1000):
+        cq0 = _init(w, heads, Q, w.Cq, 0)
+        ck0 = _init(w, heads, K, Ck, 1)
+        ws = torch.empty(svg2.svg2_forward_workspace_size(svg2.SVG2_BF16, H, w.N, w.d, w.Cq, Ck, False, False),
+                         dtype=torch.uint8, device="cuda")
+        out = torch.empty_like(Qd0)
+        for p in (0.5, 0.6, 0.7, 0.8, 0.9, 0.95, 0.99):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(1000 + w.seed)
+            Qd, Kd = Qd0.clone(), Kd0.clone()
+            cq, ck = cq0.clone(), ck0.clone()
+            t0 = t_rest = t_km = t_at = dens = 0.0
+            for step in range(steps):
+                if step:
+                    Qd = (Qd.float() + 0.05 * torch.randn(Qd.shape, generator=g, device="cuda")).to(Qd.dtype)
+                    Kd = (Kd.float() + 0.05 * torch.randn(Kd.shape, generator=g, device="cuda")).to(Kd.dtype)
+                iters = w.iters if step == 0 else 2
+                svg2.svg2_profile_enable(True)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                res = svg2.svg2_forward(Qd, Kd, Vd, cq, ck, p, iters, want_aux=True, out=out, ws=ws)
+                e1.record()
+                torch.cuda.synchronize()
+                st, _ = svg2.svg2_profile_read()
+                svg2.svg2_profile_enable(False)
+                ms = e0.elapsed_time(e1)
+                if step == 0:
+                    t0 = ms
+                else:
+                    t_rest += ms / (steps - 1)
+                    t_km += (st["kmeans_q"] + st["kmeans_k"]) / (steps - 1)
+                    t_at += st["attn"] / (steps - 1)
+                    dens += res.aux.density.double().mean().item() / (steps - 1)
+            # last step: how far is the 2-iteration warm start from settled labels, and the recall of the selection
+            one = svg2.svg2_kmeans(Kd, ck.clone(), 1)
+            moved = (one.labels != res.aux.labels_k).float().mean().item()
+            lse_all = _dense_lse(svg2, Qd, Kd, Vd)
+            rec = svg2.svg2_attention_recall(res.aux.lse, lse_all, want_rows=False).mean.double().mean().item()
+            torch.cuda.synchronize()
+            print("| %d | %.2f | %.4f | %.2f | %.2f | %.2f | %.2f | %.0f | %.4f | %.2f %% |" %
+                  (Ck, p, dens, t0, t_rest, t_km, t_at, flops * dens / t_at / 1e9, rec, 100.0 * moved))
+            del lse_all, res, one
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=("recall", "clusters", "seeding", "fp8"))
+    ap.add_argument("what", choices=("recall", "clusters", "seeding", "fp8", "sequence"))
     ap.add_argument("--workload", default="wan_like", choices=sorted(wl.WORKLOADS))
     ap.add_argument("--heads", type=int, default=8)
     args = ap.parse_args()
@@ -223,7 +285,7 @@ def main():
     svg2.load_library()
     if not torch.cuda.is_available():
         raise RuntimeError("diagnostics need a GPU")
-    {"recall": recall, "clusters": clusters, "seeding": seeding, "fp8": fp8}[args.what](args)
+    {"recall": recall, "clusters": clusters, "seeding": seeding, "fp8": fp8, "sequence": sequence}[args.what](args)
 
 
 if __name__ == "__main__":
