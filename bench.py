@@ -135,7 +135,7 @@ def main():
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE MI355X; the path shards by head with no exchange "
-              "inside it (see DESIGN.md), so --gpus %d is not run" % args.gpus, file=sys.stderr)
+              "inside it, so --gpus %d is not run" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     def log(msg):
