@@ -61,9 +61,14 @@ __global__ void kmeans_finalize_kernel(const float *__restrict__ init, float *__
         const int cnt = offsets[(size_t)h * (C + 1) + j + 1] - offsets[(size_t)h * (C + 1) + j];
         const int p0 = first_piece[(size_t)h * (C + 1) + j], p1 = first_piece[(size_t)h * (C + 1) + j + 1];
         float s = (mode == 2) ? csum[idx] : 0.f;
+        // the pieces are added in their order, one after the other (the result does not depend on how the loop is
+        // unrolled); unrolled, the loads of 8 pieces are in flight together -- the largest cluster of a head has
+        // dozens of pieces and its block decides how long the launch takes
+#pragma unroll 8
         for (int q = p0; q < p1; ++q) s += psum[((size_t)h * max_pieces + q) * d + k];
         if (mode == 2) {
             const int o0 = first_piece_old[(size_t)h * (C + 1) + j], o1 = first_piece_old[(size_t)h * (C + 1) + j + 1];
+#pragma unroll 8
             for (int q = o0; q < o1; ++q) s -= psum_old[((size_t)h * max_pieces + q) * d + k];
         }
         if (cnt > 0) {

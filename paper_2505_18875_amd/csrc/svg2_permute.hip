@@ -107,10 +107,21 @@ __global__ __launch_bounds__(64) void permute_scatter_kernel(const int32_t *__re
     const int n0 = chunk * PERM_CHUNK;
     const int n1 = min(N, n0 + PERM_CHUNK);
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    for (int g = n0; g < n1; g += 64) {
+    // all labels of the chunk are requested up front (one memory round trip instead of one per group of 64)
+    constexpr int NG = PERM_CHUNK / 64;
+    int lr[NG];
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+        const int n = n0 + i * 64 + lane;
+        lr[i] = (n < n1) ? lab[n] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+        const int g = n0 + i * 64;
+        if (g >= n1) break;
         const int n = g + lane;
         const bool valid = n < n1;
-        const int l = valid ? lab[n] : 0;
+        const int l = lr[i];
         // lanes holding the same label as this one
         unsigned long long peers = __ballot(valid);
         for (int b = 0; b < nbits; ++b) {
