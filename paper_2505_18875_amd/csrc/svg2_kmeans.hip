@@ -453,12 +453,23 @@ __global__ __launch_bounds__(256) void kmeans_segsum_delta_kernel(const T *__res
     int32_t *list = s_list[wave];
     const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
     int cnt = 0;
-    for (int r = 0; r < nrows; r += 64) {
-        const int rr = r + lane;
-        const int src = (rr < nrows) ? pm[row0 + rr] : 0;
-        const bool take = rr < nrows && ot[src] != cl;
+    // the rows of the piece and then their other labels are requested together: two memory round trips for the
+    // piece instead of two per 64 rows
+    constexpr int NG = KM_SEG / 64;
+    int srcs[NG], oth[NG];
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+        const int rr = i * 64 + lane;
+        srcs[i] = (rr < nrows) ? pm[row0 + rr] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < NG; ++i) oth[i] = ot[srcs[i]];
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+        if (i * 64 >= nrows) break;
+        const bool take = i * 64 + lane < nrows && oth[i] != cl;
         const unsigned long long m = __ballot(take);
-        if (take) list[cnt + __popcll(m & lt_mask)] = src;
+        if (take) list[cnt + __popcll(m & lt_mask)] = srcs[i];
         cnt += __popcll(m);
     }
     float acc[EPL];
