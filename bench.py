@@ -34,7 +34,7 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0           # MI355X dense fp8 MFMA peak
 # HBM-side bytes per attention-kernel launch on the Wan-like layer at top-p 0.9, from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy in the
 # same runs): profiles/wan_like_attention_hbm_traffic.md.  Other workloads report null.
-ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 17100091.6 + 1031151.7) * 1024.0}
+ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 17320346.2 + 1034588.3) * 1024.0}
 
 
 def _gen_head(args):

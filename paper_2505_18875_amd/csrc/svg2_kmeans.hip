@@ -36,8 +36,8 @@ static constexpr int KM_WG_TOKENS = KM_NW * KM_TB * 32;
 static constexpr int KM_IB = 8;        // token blocks per work item (bf16 kernel)
 static constexpr int KM_UB = 4;        // load instructions in flight per wavefront in the segmented sum
 static constexpr int KM_SEG = 256;     // rows per piece of the segmented sum
-static constexpr int KM_FULL_FIRST = 2; // iterations whose update step sums every cluster afresh ...
-static constexpr int KM_FULL_EVERY = 8; // ... and again every so many iterations (bounds the rounding drift of the delta update)
+static constexpr int KM_FULL_FIRST = 1; // iterations whose update step sums every cluster afresh ...
+static constexpr int KM_FULL_EVERY = 16; // ... and again every so many iterations (bounds the rounding drift of the delta update)
 
 // ---------------------------------------------------------------- finalize
 // grid (C, H), block d.  mode 0: centroids <- init (first call).  mode 1: cluster sum = sum of the cluster's
@@ -576,8 +576,8 @@ static int kmeans_run(const T *X, int H, int N, int C, int iters, const float *i
     for (int t = 0; t < iters; ++t) {
         float *obj = objective ? objective + t : nullptr;
         // Update step: the first KM_FULL_FIRST iterations, and every KM_FULL_EVERY-th after that, sum every
-        // cluster afresh; the others only move the tokens whose label changed (a few per cent from the third
-        // iteration on) between the cluster sums, which reads a tenth of X.
+        // cluster afresh; the others only move the tokens whose label changed (a quarter in the second
+        // iteration, a few per cent from the third on) between the cluster sums, which reads a fraction of X.
         const bool full = t < KM_FULL_FIRST || t % KM_FULL_EVERY == 0;
         const int s = t & 1;
         // the labels of iteration t go to the caller's buffer when iters - 1 - t is even, else to the scratch
