@@ -157,6 +157,38 @@ def test_sparse_attn_fp8_ragged_and_empty_clusters(svg2, oracle):
         assert rows.size and np.all(O[rows] == 0.0) and np.all(np.isneginf(lse[rows]))
 
 
+def test_sparse_attn_fp8_thousands_of_short_key_clusters(svg2, oracle):
+    """Key clusters of one or two rows: a 64-key tile crosses dozens of runs of the virtual key sequence, and the row
+    look-up of a tile starts from the run the plan recorded for it."""
+    r = np.random.default_rng(78)
+    N, d, Cq, Ck = 4200, 128, 3, 2700
+    Q, K, V = (wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32)) for _ in range(3))
+    lq = r.integers(0, Cq, size=N).astype(np.int32)
+    lk = r.integers(0, Ck, size=N).astype(np.int32)
+    sel = [np.sort(r.choice(Ck, size=2600, replace=False)), np.sort(r.choice(Ck, size=1500, replace=False)),
+           np.array([5, 900, 2699], dtype=np.int64)]
+    pq, pk = oracle.permute(lq, Cq), oracle.permute(lk, Ck)
+    row_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sel])]).astype(np.int32)
+    col = np.zeros(Cq * Ck, dtype=np.int32)
+    cat = np.concatenate(sel).astype(np.int32)
+    col[: cat.size] = cat
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, to_dev(Q[None], "bf16"), to_dev(K[None], "bf16"),
+                                                 to_dev(V[None], "bf16"))
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, to_dev(pq.offsets[None]), to_dev(pk.offsets[None]),
+                                    to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
+                                    to_dev(pk.perm[None]), want_lse=True)
+    torch.cuda.synchronize()
+    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
+    O_ref, lse_ref = oracle.sparse_attention(dq[1][pq.perm], dk[1][pk.perm], dv[1][pk.perm], pq.offsets, pk.offsets,
+                                             row_ptr, cat, perm_q=pq.perm,
+                                             scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
+    O_ref *= float(dv[2])
+    O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    fin = np.isfinite(lse_ref)                                  # a query cluster whose 3 key clusters are all empty has no keys
+    _check_against(O[fin], lse[fin], O_ref[fin], lse_ref[fin], np.arange(int(fin.sum())), np.abs(V).max())
+    assert np.all(O[~fin] == 0.0) and np.all(np.isneginf(lse[~fin]))
+
+
 def test_sparse_attn_fp8_dense_special_case_flat_and_peaked_rows(svg2, oracle):
     # one cluster on each side = dense attention.  Half of the queries are tiny (flat softmax over 3000 keys:
     # every probability is about 2^-11.5 of the sum and must not be flushed to zero), half are large (peaked).
