@@ -105,6 +105,29 @@ int svg2_permute(const int32_t *labels, int H, int N, int C,
                  int dtype, int d, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
+ * svg2_permute_noalloc -- svg2_permute for callers that cannot allocate device
+ * memory or size a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid the allocator.  Same arguments (minus the
+ * workspace) and bit-identical results; the sort's scratch (one int32 per head,
+ * chunk of 1024 tokens and cluster) lives in an array of
+ * SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES inside the library, which every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing,
+ * frees nothing and only enqueues kernels on `stream`.
+ *   Limit: H * ceil(N / 1024) * C * 4 <= SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES,
+ *   else SVG2_WORKSPACE_TOO_SMALL and nothing is launched (the Wan-like K side,
+ *   H = 40, N = 75,600, C = 500, needs 5.9 MB).
+ *   Every call on one GPU uses the same array: calls that overlap in time on
+ *   one GPU (different streams, different threads) race and must be serialised
+ *   by the caller; calls on one stream are ordered and safe.  Stale contents of
+ *   the array never matter (every entry that is read is written first).
+ * ------------------------------------------------------------------------- */
+#define SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES (16u << 20)
+int svg2_permute_noalloc(const int32_t *labels, int H, int N, int C,
+                         int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                         int n_tensors, const void *const *src, void *const *dst,
+                         int dtype, int d, void *stream);
+
+/* ---------------------------------------------------------------------------
  * svg2_select_topp -- Section 4.2: S_ij = cq_i . ck_j / sqrt(d) (Eq. 1),
  * P'_ij = |K_j| exp(S_ij) / sum_k |K_k| exp(S_ik) (Eq. 2); for each query
  * cluster the key clusters are taken in descending P' until the accumulated

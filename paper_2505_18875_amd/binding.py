@@ -25,7 +25,7 @@ MAX_CLUSTERS = 4096
 EXPORTS = (
     "svg2_last_error", "svg2_version",
     "svg2_kmeans_workspace_size", "svg2_kmeans",
-    "svg2_permute_workspace_size", "svg2_permute",
+    "svg2_permute_workspace_size", "svg2_permute", "svg2_permute_noalloc",
     "svg2_select_topp_workspace_size", "svg2_select_topp",
     "svg2_sparse_attn_workspace_size", "svg2_sparse_attn", "svg2_sparse_attn_gather_free",
     "svg2_forward_workspace_size", "svg2_forward",
@@ -73,6 +73,7 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_kmeans.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.svg2_permute_workspace_size.argtypes = [i, i, i]
         lib.svg2_permute.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, i, i, vp, sz, vp]
+        lib.svg2_permute_noalloc.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, i, i, vp]
         lib.svg2_select_topp_workspace_size.argtypes = [i, i, i]
         lib.svg2_select_topp.argtypes = [vp, vp, vp, vp, i, i, i, i, f, vp, vp, vp, vp, vp, sz, vp]
         lib.svg2_sparse_attn_workspace_size.argtypes = [i, i, i, i, i, i]
@@ -177,6 +178,31 @@ def svg2_permute(labels, C, tensors=(), *, want_inverse=True, ws=None):
     _check(lib.svg2_permute(_dev(labels, torch.int32, "labels"), H, N, C, _dev(offsets), _dev(perm), _dev(inv),
                             n, src, dst, dt, d, _dev(ws), ws.numel(), _stream()))
     return SimpleNamespace(offsets=offsets, perm=perm, inv_perm=inv, tensors=outs)
+
+
+def svg2_permute_noalloc(labels, C, offsets, perm, inv_perm=None, tensors=(), outs=()):
+    """svg2_permute on the library's built-in scratch: every buffer is the caller's, nothing is allocated here
+    or in the library.  labels [H,N] int32; offsets [H,C+1], perm [H,N], inv_perm [H,N] or None int32 outputs;
+    outs[t] receives the permuted copy of tensors[t]."""
+    lib = load_library()
+    H, N = labels.shape
+    n = len(tensors)
+    if len(outs) != n:
+        raise ValueError("one output per tensor")
+    dt, d = (SVG2_F32, 0)
+    src = dst = None
+    if n:
+        dt, d = _dtype_code(tensors[0]), tensors[0].shape[-1]
+        for t, o in zip(tensors, outs):
+            if t.shape != (H, N, d) or _dtype_code(t) != dt or o.shape != t.shape or o.dtype != t.dtype:
+                raise ValueError("tensors and outs must all be [H,N,d] of one dtype")
+            _dev(t, name="tensor")
+            _dev(o, name="out")
+        src = (ctypes.c_void_p * n)(*[t.data_ptr() for t in tensors])
+        dst = (ctypes.c_void_p * n)(*[t.data_ptr() for t in outs])
+    _check(lib.svg2_permute_noalloc(_dev(labels, torch.int32, "labels"), H, N, C, _dev(offsets, torch.int32, "offsets"),
+                                    _dev(perm, torch.int32, "perm"), _dev(inv_perm, torch.int32, "inv_perm"),
+                                    n, src, dst, dt, d, _stream()))
 
 
 def svg2_select_topp(cq, ck, counts_q, counts_k, top_p, *, want_p_est=False, ws=None):

@@ -210,6 +210,34 @@ int svg2_permute(const int32_t *labels, int H, int N, int C, int32_t *offsets, i
                           static_cast<hipStream_t>(stream));
 }
 
+int svg2_permute_noalloc(const int32_t *labels, int H, int N, int C, int32_t *offsets, int32_t *perm,
+                         int32_t *inv_perm, int n_tensors, const void *const *src, void *const *dst, int dtype, int d,
+                         void *stream)
+{
+    clear_error();
+    SVG2_REQUIRE(H >= 1 && H <= 65535 && N >= 1, SVG2_INVALID_ARG, "H = %d (1..65535) and N = %d must be positive", H, N);
+    SVG2_REQUIRE(C >= 1 && C <= SVG2_MAX_CLUSTERS, SVG2_INVALID_ARG, "C = %d must be in 1..%d", C, SVG2_MAX_CLUSTERS);
+    SVG2_REQUIRE(labels && offsets && perm, SVG2_INVALID_ARG, "labels, offsets and perm must be non-null");
+    SVG2_REQUIRE(n_tensors >= 0 && n_tensors <= 2, SVG2_INVALID_ARG, "n_tensors = %d must be 0, 1 or 2", n_tensors);
+    if (n_tensors > 0) {
+        SVG2_TRY(check_common(dtype, H, N, d));
+        SVG2_REQUIRE(src && dst, SVG2_INVALID_ARG, "src and dst must be non-null when n_tensors > 0");
+        for (int t = 0; t < n_tensors; ++t) {
+            SVG2_REQUIRE(src[t] && dst[t], SVG2_INVALID_ARG, "src[%d] / dst[%d] is null", t, t);
+            SVG2_REQUIRE(src[t] != dst[t], SVG2_INVALID_ARG, "dst[%d] must not alias src[%d]", t, t);
+        }
+    }
+    const size_t need = permute_ws_bytes(H, N, C);
+    SVG2_REQUIRE(need <= (size_t)SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES, SVG2_WORKSPACE_TOO_SMALL,
+                 "svg2_permute_noalloc: H = %d, N = %d, C = %d needs %zu bytes of scratch, the built-in array has %zu "
+                 "(use svg2_permute with a workspace)",
+                 H, N, C, need, (size_t)SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES);
+    void *scratch_ptr = nullptr;
+    SVG2_TRY(permute_static_scratch(&scratch_ptr));
+    return permute_launch(labels, H, N, C, offsets, perm, inv_perm, n_tensors, src, dst, dtype, d, scratch_ptr,
+                          static_cast<hipStream_t>(stream));
+}
+
 size_t svg2_select_topp_workspace_size(int H, int Cq, int Ck)
 {
     if (H < 1 || Cq < 1 || Ck < 1 || Cq > SVG2_MAX_CLUSTERS || Ck > SVG2_MAX_CLUSTERS) return 256;

@@ -78,6 +78,9 @@ int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets,
                    int32_t *inv_perm, int n_tensors, const void *const *src, void *const *dst,
                    int dtype, int d, void *ws, hipStream_t st);
 
+// device address (on the current device) of the library's own scratch array for svg2_permute_noalloc
+int permute_static_scratch(void **out);
+
 size_t select_ws_bytes(int H, int Cq, int Ck);
 int select_launch(const float *cq, const float *ck, const int32_t *counts_q, const int32_t *counts_k,
                   int H, int Cq, int Ck, int d, float top_p, int32_t *row_ptr, int32_t *col_idx,

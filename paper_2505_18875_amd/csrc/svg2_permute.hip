@@ -11,11 +11,19 @@
 //            the write side
 //
 // Everything is integer work: results are unique and reproducible bit for bit.
+#include <mutex>
+
 #include "svg2_common.h"
 
 namespace svg2 {
 
 static constexpr int PERM_CHUNK = 1024;     // tokens per chunk (one wavefront in scatter)
+
+// Scratch of svg2_permute_noalloc: the per-(head, chunk, cluster) histogram of the counting sort lives in this
+// file-scope array instead of a caller's workspace.  Every GPU the library runs on holds its own copy until the
+// process ends.  In host code the name is only a handle: the device address is looked up once per device
+// (hipGetSymbolAddress) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[SVG2_PERMUTE_NOALLOC_SCRATCH_BYTES];
 
 __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t *__restrict__ labels, int N, int C,
                                                            int nchunks, int32_t *__restrict__ hist)
@@ -198,6 +206,28 @@ int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets,
                            perm, N, lanes_per_row, rows_per_block);
     }
     SVG2_HIP_CHECK(hipGetLastError());
+    return SVG2_OK;
+}
+
+// Device address of `scratch` on the current device (looked up on the first call per device, then kept).
+static constexpr int PERM_MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[PERM_MAX_DEVICES] = {};
+
+int permute_static_scratch(void **out)
+{
+    int dev = -1;
+    SVG2_HIP_CHECK(hipGetDevice(&dev));
+    SVG2_REQUIRE(dev >= 0 && dev < PERM_MAX_DEVICES, SVG2_INVALID_ARG, "device ordinal %d is outside 0..%d", dev,
+                 PERM_MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        SVG2_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        SVG2_REQUIRE(p != nullptr, SVG2_HIP_ERROR, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return SVG2_OK;
 }
 

@@ -66,6 +66,9 @@ def test_workspace_queries_and_validation_run_on_the_host(lib):
     assert rc == 1 and b"top_p" in lib.svg2_last_error()
     rc = lib.svg2_permute(one, 1, 16, 5000, one, one, None, 0, None, None, 0, 0, one, 1 << 20, None)
     assert rc == 1
+    # the entry point that allocates nothing rejects sizes beyond its built-in scratch before it touches the GPU
+    rc = lib.svg2_permute_noalloc(one, 40, 75600, 4096, one, one, None, 0, None, None, 0, 0, None)
+    assert rc == 3 and b"scratch" in lib.svg2_last_error()
     rc = lib.svg2_sparse_attn(one, one, one, 1, 1, 16, 128, 1, 1, one, one, one, one, None, 0.0, one, None, one,
                               1 << 20, None)
     assert rc == 1 and b"alias" in lib.svg2_last_error()
