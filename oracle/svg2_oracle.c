@@ -15,6 +15,7 @@
  *   attention recall           Section 3.1 (attention mass the selected keys capture)
  *   k-means++ seeding          Section 4.3 / 5.3 (the initialisation the paper starts from)
  *   FP8 E4M3 quantisation      Table 1, "+ FP8" rows (per-head scaling: a reading, the paper gives no recipe)
+ *   rounded-weights budget     error bound of a weighted mean whose weights are rounded (tests of the FP8 path)
  *
  * Inputs are float arrays (bf16 workloads pass bf16-representable floats, so
  * reading them is exact); every sum is accumulated in double.  OpenMP is used
@@ -382,6 +383,107 @@ void svg2o_sparse_attention(const float *Qp, const float *Kp, const float *Vp,
             if (lse) lse[dst] = (cnt > 0) ? mx + log(den) : -INFINITY;
         }
         free(s); free(acc);
+    }
+    free(cl);
+}
+
+/* ------------------------------------------------------------------------
+ * Error budget of block-sparse attention whose probabilities are ROUNDED
+ * before they multiply V (the "+ FP8" rows of Table 1 under this build's
+ * reading: probabilities enter the second product as E4M3).  This is a bound
+ * calculator for tests, derived from the mathematics of a weighted mean, not a
+ * model of any kernel's blocking or order.
+ *
+ * For one query row with exact probabilities pi_j (softmax over the selected
+ * keys, Section 4.3), values v_jc and exact output O_c = sum_j pi_j v_jc:
+ * if every weight is replaced by w_j = pi_j (1 + e_j) and the result is
+ * renormalised by sum_j w_j (the row sum is taken over the rounded weights),
+ *     O'_c - O_c = sum_j pi_j e_j (v_jc - O_c) / (1 + sum_j pi_j e_j).
+ * Hence, with |e_j| <= eps for every key,
+ *     |O'_c - O_c| <= eps / (1 - eps) * dev1[c],  dev1[c] = sum_j pi_j |v_jc - O_c|,
+ * and if the e_j are independent and uniform in [-eps, eps] the error has
+ * standard deviation  eps / sqrt(3) * sqrt(dev2[c]),  dev2[c] = sum_j pi_j^2 (v_jc - O_c)^2.
+ * Weights far below the row maximum may be rounded with an ABSOLUTE rather
+ * than a relative error (subnormal range of the 8-bit format); for those the
+ * caller needs  tail1[c] = sum_{j: pi_j < tail_ratio * max_j pi_j} |v_jc - O_c|  and
+ * tail2[c], the same sum of squares: an absolute weight error a (relative to the
+ * row sum) per such key adds at most a * tail1[c], or a / sqrt(3) * sqrt(tail2[c])
+ * in standard deviation.
+ *
+ * Same arguments as svg2o_sparse_attention; rows != NULL restricts the rows.
+ * Outputs, each [N,d] doubles indexed like O (original row if perm_q is given),
+ * untouched for rows not computed: dev1, dev2, tail1, tail2.
+ * ------------------------------------------------------------------------ */
+void svg2o_rounded_weights_budget(const float *Qp, const float *Kp, const float *Vp,
+                                  int N, int d, int Cq, int Ck,
+                                  const int32_t *offsets_q, const int32_t *offsets_k,
+                                  const int32_t *row_ptr, const int32_t *col_idx,
+                                  const int32_t *perm_q, double scale, double tail_ratio,
+                                  const int32_t *rows, int n_rows,
+                                  double *dev1, double *dev2, double *tail1, double *tail2)
+{
+    (void)Ck;
+    int total = rows ? n_rows : N;
+    int32_t *cl = (int32_t *)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    for (int i = 0; i < Cq; ++i)
+        for (int r = offsets_q[i]; r < offsets_q[i + 1]; ++r) cl[r] = i;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 8)
+        for (int t = 0; t < total; ++t) {
+            int r = rows ? rows[t] : t;
+            int i = cl[r];
+            const float *q = Qp + (size_t)r * d;
+            int cnt = 0;
+            double mx = -INFINITY;
+            for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                int j = col_idx[e];
+                for (int m = offsets_k[j]; m < offsets_k[j + 1]; ++m) {
+                    const float *k = Kp + (size_t)m * d;
+                    double a = 0.0;
+                    for (int c = 0; c < d; ++c) a += (double)q[c] * (double)k[c];
+                    a *= scale;
+                    s[cnt++] = a;
+                    if (a > mx) mx = a;
+                }
+            }
+            /* exact probabilities and exact output */
+            double den = 0.0;
+            for (int u = 0; u < cnt; ++u) { s[u] = exp(s[u] - mx); den += s[u]; }
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            cnt = 0;
+            for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                int j = col_idx[e];
+                for (int m = offsets_k[j]; m < offsets_k[j + 1]; ++m) {
+                    const float *v = Vp + (size_t)m * d;
+                    s[cnt] /= den;                       /* pi_j; the largest is 1 / den */
+                    for (int c = 0; c < d; ++c) o[c] += s[cnt] * (double)v[c];
+                    cnt += 1;
+                }
+            }
+            size_t dst = (size_t)(perm_q ? perm_q[r] : r);
+            double *a1 = dev1 + dst * d, *a2 = dev2 + dst * d, *b1 = tail1 + dst * d, *b2 = tail2 + dst * d;
+            for (int c = 0; c < d; ++c) a1[c] = a2[c] = b1[c] = b2[c] = 0.0;
+            double pmax = (cnt > 0) ? 1.0 / den : 0.0;
+            cnt = 0;
+            for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                int j = col_idx[e];
+                for (int m = offsets_k[j]; m < offsets_k[j + 1]; ++m) {
+                    const float *v = Vp + (size_t)m * d;
+                    double p = s[cnt++];
+                    int in_tail = p < tail_ratio * pmax;
+                    for (int c = 0; c < d; ++c) {
+                        double dv = fabs((double)v[c] - o[c]);
+                        a1[c] += p * dv;
+                        a2[c] += p * p * dv * dv;
+                        if (in_tail) { b1[c] += dv; b2[c] += dv * dv; }
+                    }
+                }
+            }
+        }
+        free(s); free(o);
     }
     free(cl);
 }

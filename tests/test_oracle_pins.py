@@ -227,6 +227,35 @@ def test_select_hand_worked_example(oracle):
     np.testing.assert_array_equal(res.col_idx, [0, 3])
 
 
+def test_select_margin_is_set_by_the_gap_between_last_kept_and_first_dropped(oracle):
+    # zero centroids -> P' is the size share 0.5, 0.25, 0.249, 0.001.  At p = 0.7 the kept clusters are {0, 1}:
+    # mass before the last kept 0.5 (0.2 from p), mass including it 0.75 (0.05 from p), but the first dropped
+    # cluster is within (0.25 - 0.249) / 0.25 = 0.004 of the last kept: the relative P' gap is what makes the
+    # decision fragile, so it is the margin
+    cq = np.zeros((1, 4)); ck = np.zeros((4, 4))
+    counts_k = np.array([500, 250, 249, 1])
+    res = oracle.select_topp(cq, ck, None, counts_k, 0.7)
+    np.testing.assert_array_equal(res.col_idx, [0, 1])
+    np.testing.assert_allclose(res.margin, [0.004], rtol=1e-9)
+    # the same sizes at p = 0.755: {0, 1, 2} kept (0.75 < 0.755), the mass including the last kept is 0.999;
+    # |0.75 - 0.755| = 0.005 binds, not the gap to the 0.001 cluster ((0.249 - 0.001) / 0.249 = 0.996)
+    res = oracle.select_topp(cq, ck, None, counts_k, 0.755)
+    np.testing.assert_array_equal(res.col_idx, [0, 1, 2])
+    np.testing.assert_allclose(res.margin, [0.005], rtol=1e-9)
+    # an empty cluster between them is never "the first dropped": sizes 500, 250, 0, 249, 1 give the same margin
+    res = oracle.select_topp(cq, np.zeros((5, 4)), None, np.array([500, 250, 0, 249, 1]), 0.7)
+    np.testing.assert_array_equal(res.col_idx, [0, 1])
+    np.testing.assert_allclose(res.margin, [0.004], rtol=1e-9)
+    # everything kept: nothing is dropped, so only the two mass terms count (p = 0.9995: |0.999 - p| = 0.0005)
+    res = oracle.select_topp(cq, ck, None, counts_k, 0.9995)
+    np.testing.assert_array_equal(res.col_idx, [0, 1, 2, 3])
+    np.testing.assert_allclose(res.margin, [0.0005], rtol=1e-6)
+    # an exact tie between last kept and first dropped (equal sizes): margin 0, the lower index is kept
+    res = oracle.select_topp(cq, ck, None, np.array([400, 200, 200, 200]), 0.55)
+    np.testing.assert_array_equal(res.col_idx, [0, 1])
+    np.testing.assert_allclose(res.margin, [0.0], atol=1e-15)
+
+
 def test_select_probabilities(oracle):
     r = _rng(9)
     cq, ck = r.standard_normal((7, 16)), r.standard_normal((19, 16))
@@ -597,3 +626,79 @@ def test_quantize_e4m3_scale_and_error_bound(oracle):
     # all-zero input: scale 1, codes 0
     c0, d0, s0 = oracle.quantize_e4m3(np.zeros((4, 8), dtype=np.float32))
     assert s0 == 1.0 and not c0.any() and not d0.any()
+
+
+# ------------------------------------------------------------------ error budget of rounded probabilities
+
+def _budget_case(oracle, seed, N=90, d=6, Cq=4, Ck=7):
+    r = _rng(seed)
+    Q, K, V = (r.standard_normal((N, d)).astype(np.float32) for _ in range(3))
+    Q *= 2.0
+    lq, lk = _random_partition(r, N, Cq), _random_partition(r, N, Ck)
+    pq, pk = oracle.permute(lq, Cq), oracle.permute(lk, Ck)
+    sel = [np.sort(r.choice(Ck, size=r.integers(1, Ck), replace=False)) for _ in range(Cq)]
+    row_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sel])]).astype(np.int32)
+    col_idx = np.concatenate(sel).astype(np.int32)
+    args = (Q[pq.perm], K[pk.perm], V[pk.perm], pq.offsets, pk.offsets, row_ptr, col_idx)
+    return r, Q, K, V, lq, lk, sel, pq, args
+
+
+def test_rounded_weights_budget_bounds_every_perturbation_and_is_attained(oracle):
+    # brute force: library softmax over the selected keys, weights perturbed by relative errors within eps and
+    # renormalised by their own sum.  No perturbation may move an output by more than eps / (1 - eps) * dev1, and
+    # the adversarial one (every weight pushed towards the side of its value) comes within 1 / (1 + eps) of it.
+    r, Q, K, V, lq, lk, sel, pq, args = _budget_case(oracle, 31)
+    eps, d = 2.0 ** -4, Q.shape[1]
+    dev1, dev2, _, _ = oracle.rounded_weights_budget(*args, perm_q=pq.perm)
+    O, _ = oracle.sparse_attention(*args, perm_q=pq.perm)
+    for n in range(0, Q.shape[0], 7):
+        keys = np.nonzero(np.isin(lk, sel[lq[n]]))[0]
+        pi = scipy.special.softmax(K[keys].astype(np.float64) @ Q[n].astype(np.float64) / np.sqrt(d))
+        v = V[keys].astype(np.float64)
+        for trial in range(40):
+            e = r.uniform(-eps, eps, size=keys.size)
+            w = pi * (1 + e)
+            err = (w @ v) / w.sum() - O[n]
+            assert np.all(np.abs(err) <= eps / (1 - eps) * dev1[n] + 1e-15)
+        for c in range(d):
+            w = pi * (1 + eps * np.sign(v[:, c] - O[n, c]))
+            err = (w @ v[:, c]) / w.sum() - O[n, c]
+            assert err >= eps / (1 + eps) * dev1[n, c] - 1e-15
+        # independent uniform errors: the spread is eps / sqrt(3) * sqrt(dev2) to first order in eps
+        small = 1e-3
+        errs = np.stack([((pi * (1 + e)) @ v) / (pi * (1 + e)).sum() - O[n]
+                         for e in r.uniform(-small, small, size=(4000, keys.size))])
+        np.testing.assert_allclose(errs.std(axis=0), small / np.sqrt(3) * np.sqrt(dev2[n]), rtol=0.08)
+
+
+def test_rounded_weights_budget_closed_forms_and_tail(oracle):
+    # two keys with probabilities a, 1 - a and values x, y: O = a x + (1 - a) y, so dev1 = 2 a (1 - a) |x - y|
+    # and dev2 = (a^2 (1 - a)^2 + (1 - a)^2 a^2) (x - y)^2
+    d = 4
+    Q = np.zeros((1, d), np.float32); Q[0, 0] = 2.0
+    K = np.zeros((2, d), np.float32); K[0, 0] = np.log(3.0)            # scores ln 3 and 0 at scale 1/2 -> a = 3/4
+    V = np.array([[1.0, -2.0, 0.5, 0.0], [3.0, 2.0, 0.5, 0.0]], np.float32)
+    one = np.array([0, 1], np.int32)
+    two = np.array([0, 2], np.int32)
+    dev1, dev2, t1, t2 = oracle.rounded_weights_budget(Q, K, V, one, two, one, np.zeros(1, np.int32), tail_ratio=0.5)
+    a, diff = 0.75, np.abs(V[0] - V[1]).astype(np.float64)         # ln 3 is stored as float32: a = 3/4 to ~1e-8
+    np.testing.assert_allclose(dev1[0], 2 * a * (1 - a) * diff, rtol=1e-7)
+    np.testing.assert_allclose(dev2[0], 2 * (a * (1 - a)) ** 2 * diff ** 2, rtol=1e-7)
+    # the second key has a third of the largest probability: it is the tail at ratio 0.5; its |v - O| = a |x - y|
+    np.testing.assert_allclose(t1[0], a * diff, rtol=1e-7)
+    np.testing.assert_allclose(t2[0], (a * diff) ** 2, rtol=1e-7)
+    # a weighted mean of equal values cannot be wrong whatever the weights: column 2 and 3 have no budget at all
+    assert dev1[0, 2] == 0.0 and dev1[0, 3] == 0.0 and t1[0, 3] == 0.0
+    # tail sums by brute force against library softmax; sampled rows leave the others untouched
+    r, Q, K, V, lq, lk, sel, pq, args = _budget_case(oracle, 32)
+    rows = np.array([1, 40, 77], dtype=np.int32)
+    _, _, t1, t2 = oracle.rounded_weights_budget(*args, perm_q=pq.perm, rows=rows, tail_ratio=0.05)
+    O, _ = oracle.sparse_attention(*args, perm_q=pq.perm)
+    for n in pq.perm[rows]:
+        keys = np.nonzero(np.isin(lk, sel[lq[n]]))[0]
+        pi = scipy.special.softmax(K[keys].astype(np.float64) @ Q[n].astype(np.float64) / np.sqrt(Q.shape[1]))
+        tail = pi < 0.05 * pi.max()
+        dv = np.abs(V[keys][tail].astype(np.float64) - O[n])
+        np.testing.assert_allclose(t1[n], dv.sum(axis=0), rtol=1e-10, atol=1e-14)
+        np.testing.assert_allclose(t2[n], (dv ** 2).sum(axis=0), rtol=1e-10, atol=1e-14)
+    assert np.isnan(np.delete(t1, pq.perm[rows], axis=0)).all()
