@@ -21,8 +21,12 @@
  *     read-back of device values, launch sizes depend on the arguments
  *     alone), so it may be recorded into a HIP graph and replayed; stale
  *     workspace contents never matter.
- *   - Return value: SVG2_OK or an error code.  On any error nothing has been
- *     launched and svg2_last_error() (thread-local, HOST string) says why.
+ *   - Return value: SVG2_OK or an error code; svg2_last_error() (thread-local,
+ *     HOST string) says why.  Arguments, workspace and kernel attributes are
+ *     checked before the first launch: SVG2_INVALID_ARG, SVG2_UNSUPPORTED and
+ *     SVG2_WORKSPACE_TOO_SMALL mean that nothing was enqueued and no buffer was
+ *     touched.  SVG2_HIP_ERROR can also come from a launch in the middle of a
+ *     call; outputs and in/out buffers are then undefined.
  *   - dtype is SVG2_F32 or SVG2_BF16 (storage type of Q, K, V, O); d is 64 or
  *     128; 1 <= C <= min(N, SVG2_MAX_CLUSTERS); H >= 1; N >= 1 and
  *     H*N*d < 2^40.  Accumulation is always fp32.
@@ -326,11 +330,13 @@ int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C,
  * at most SVG2_PROFILE_MAX_CALLS calls are kept, later ones go unrecorded).
  * svg2_profile_read waits for the recorded events, writes the summed
  * milliseconds per stage to stage_ms (HOST array of SVG2_N_STAGES floats, in
- * the order k-means Q, k-means K, permutation Q+K (svg2_forward_fp8: plus the
- * E4M3 quantisation of Q, K, V), selection, attention plan, attention kernel) and the number of recorded calls to n_calls (HOST), then
- * clears the record.  svg2_profile_enable(0) stops recording.
+ * the order k-means of Q and K (both sides share their launches), permutation
+ * Q+K (svg2_forward_fp8: plus the E4M3 quantisation of Q, K, V), selection,
+ * attention plan, attention kernel) and the number of recorded calls to
+ * n_calls (HOST), then clears the record.  svg2_profile_enable(0) stops
+ * recording.
  * ------------------------------------------------------------------------- */
-#define SVG2_N_STAGES 6
+#define SVG2_N_STAGES 5
 #define SVG2_PROFILE_MAX_CALLS 256
 int svg2_profile_enable(int enable);
 int svg2_profile_read(float *stage_ms, int *n_calls);

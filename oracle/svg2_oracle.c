@@ -404,23 +404,25 @@ void svg2o_sparse_attention(const float *Qp, const float *Kp, const float *Vp,
  * and if the e_j are independent and uniform in [-eps, eps] the error has
  * standard deviation  eps / sqrt(3) * sqrt(dev2[c]),  dev2[c] = sum_j pi_j^2 (v_jc - O_c)^2.
  * Weights far below the row maximum may be rounded with an ABSOLUTE rather
- * than a relative error (subnormal range of the 8-bit format); for those the
- * caller needs  tail1[c] = sum_{j: pi_j < tail_ratio * max_j pi_j} |v_jc - O_c|  and
- * tail2[c], the same sum of squares: an absolute weight error a (relative to the
- * row sum) per such key adds at most a * tail1[c], or a / sqrt(3) * sqrt(tail2[c])
- * in standard deviation.
+ * than a relative error (subnormal range of the 8-bit format, flush to zero):
+ * for a key with pi_j < tail_ratio * pi_max (pi_max = max_j pi_j) the weight
+ * error is at most a_j = min(pi_j, tail_abs * pi_max) on top of the relative
+ * one -- min(pi_j, .) because a weight cannot lose more than itself.  For those
+ *     tail1[c] = sum_tail a_j |v_jc - O_c|,  tail2[c] = sum_tail a_j^2 (v_jc - O_c)^2,
+ *     tailw    = sum_tail a_j   (what the row sum can be off by, relative to itself),
+ * and the bound becomes (eps dev1[c] + tail1[c]) / (1 - eps - tailw).
  *
  * Same arguments as svg2o_sparse_attention; rows != NULL restricts the rows.
- * Outputs, each [N,d] doubles indexed like O (original row if perm_q is given),
- * untouched for rows not computed: dev1, dev2, tail1, tail2.
+ * Outputs, indexed like O (original row if perm_q is given), untouched for
+ * rows not computed: dev1, dev2, tail1, tail2 [N,d] and tailw [N].
  * ------------------------------------------------------------------------ */
 void svg2o_rounded_weights_budget(const float *Qp, const float *Kp, const float *Vp,
                                   int N, int d, int Cq, int Ck,
                                   const int32_t *offsets_q, const int32_t *offsets_k,
                                   const int32_t *row_ptr, const int32_t *col_idx,
-                                  const int32_t *perm_q, double scale, double tail_ratio,
+                                  const int32_t *perm_q, double scale, double tail_ratio, double tail_abs,
                                   const int32_t *rows, int n_rows,
-                                  double *dev1, double *dev2, double *tail1, double *tail2)
+                                  double *dev1, double *dev2, double *tail1, double *tail2, double *tailw)
 {
     (void)Ck;
     int total = rows ? n_rows : N;
@@ -466,7 +468,8 @@ void svg2o_rounded_weights_budget(const float *Qp, const float *Kp, const float 
             size_t dst = (size_t)(perm_q ? perm_q[r] : r);
             double *a1 = dev1 + dst * d, *a2 = dev2 + dst * d, *b1 = tail1 + dst * d, *b2 = tail2 + dst * d;
             for (int c = 0; c < d; ++c) a1[c] = a2[c] = b1[c] = b2[c] = 0.0;
-            double pmax = (cnt > 0) ? 1.0 / den : 0.0;
+            double pmax = (cnt > 0) ? 1.0 / den : 0.0;      /* the largest exp(s - mx) is 1 */
+            double tw = 0.0;
             cnt = 0;
             for (int e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
                 int j = col_idx[e];
@@ -474,14 +477,17 @@ void svg2o_rounded_weights_budget(const float *Qp, const float *Kp, const float 
                     const float *v = Vp + (size_t)m * d;
                     double p = s[cnt++];
                     int in_tail = p < tail_ratio * pmax;
+                    double a = fmin(p, tail_abs * pmax);
+                    if (in_tail) tw += a;
                     for (int c = 0; c < d; ++c) {
                         double dv = fabs((double)v[c] - o[c]);
                         a1[c] += p * dv;
                         a2[c] += p * p * dv * dv;
-                        if (in_tail) { b1[c] += dv; b2[c] += dv * dv; }
+                        if (in_tail) { b1[c] += a * dv; b2[c] += a * a * dv * dv; }
                     }
                 }
             }
+            tailw[dst] = tw;
         }
         free(s); free(o);
     }

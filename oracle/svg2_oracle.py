@@ -161,26 +161,27 @@ def sparse_attention(Qp, Kp, Vp, offsets_q, offsets_k, row_ptr, col_idx, perm_q=
 
 
 def rounded_weights_budget(Qp, Kp, Vp, offsets_q, offsets_k, row_ptr, col_idx, perm_q=None, scale=None, rows=None,
-                           tail_ratio=0.0):
+                           tail_ratio=0.0, tail_abs=0.0):
     """Error budget of the block-sparse attention output when the probabilities are rounded before they multiply V
-    and the row sum is taken over the rounded values.  Returns (dev1, dev2, tail1, tail2), each [N,d] float64 indexed
-    like the attention output (NaN for rows not computed):
+    and the row sum is taken over the rounded values.  Returns (dev1, dev2, tail1, tail2, tailw); the first four
+    [N,d], tailw [N], float64, indexed like the attention output (NaN for rows not computed):
       dev1 = sum_j pi_j |v_jc - O_c|          |error| <= eps / (1 - eps) * dev1 for relative weight errors <= eps
       dev2 = sum_j pi_j^2 (v_jc - O_c)^2      error std = eps / sqrt(3) * sqrt(dev2) for independent uniform errors
-      tail1, tail2 = sum of |v_jc - O_c| and of its square over the keys with pi_j < tail_ratio * max_j pi_j."""
+      tail1, tail2, tailw: the same sums with a_j = min(pi_j, tail_abs * pi_max) in place of pi_j (tailw: of a_j
+      alone) over the keys with pi_j < tail_ratio * pi_max, whose weights may carry an absolute error a_j."""
     Qp, Kp, Vp = _f32(Qp), _f32(Kp), _f32(Vp)
     N, d = Qp.shape
     offsets_q, offsets_k = _i32(offsets_q), _i32(offsets_k)
     row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
     Cq, Ck = offsets_q.shape[0] - 1, offsets_k.shape[0] - 1
     scale = 1.0 / np.sqrt(d) if scale is None else scale
-    outs = [np.full((N, d), np.nan, dtype=np.float64) for _ in range(4)]
+    outs = [np.full((N, d), np.nan, dtype=np.float64) for _ in range(4)] + [np.full(N, np.nan, dtype=np.float64)]
     pq = None if perm_q is None else _i32(perm_q)
     rr = None if rows is None else _i32(rows)
     _load().svg2o_rounded_weights_budget(_p(Qp), _p(Kp), _p(Vp), N, d, Cq, Ck, _p(offsets_q), _p(offsets_k),
                                          _p(row_ptr), _p(col_idx), _p(pq), ctypes.c_double(scale),
-                                         ctypes.c_double(tail_ratio), _p(rr), 0 if rr is None else rr.shape[0],
-                                         *[_p(o) for o in outs])
+                                         ctypes.c_double(tail_ratio), ctypes.c_double(tail_abs), _p(rr),
+                                         0 if rr is None else rr.shape[0], *[_p(o) for o in outs])
     return tuple(outs)
 
 

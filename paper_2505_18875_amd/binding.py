@@ -36,7 +36,7 @@ EXPORTS = (
     "svg2_kmeans_pp_init_workspace_size", "svg2_kmeans_pp_init",
     "svg2_profile_enable", "svg2_profile_read",
 )
-STAGES = ("kmeans_q", "kmeans_k", "permute", "select", "attn_plan", "attn")
+STAGES = ("kmeans", "permute", "select", "attn_plan", "attn")
 
 
 class Svg2Error(RuntimeError):

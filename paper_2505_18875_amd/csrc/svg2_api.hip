@@ -57,11 +57,26 @@ static int check_ws(const void *ws, size_t have, size_t need)
     return SVG2_OK;
 }
 
-#define SVG2_TRY(expr)                    \
-    do {                                  \
-        int rc_ = (expr);                 \
-        if (rc_ != SVG2_OK) return rc_;   \
-    } while (0)
+// (kernel, device) pairs whose dynamic-LDS limit has been raised, with the size it was raised to
+struct LdsAttr {
+    const void *kernel;
+    int device;
+    size_t bytes;
+};
+static std::mutex g_lds_mu;
+static std::vector<LdsAttr> g_lds_done;
+
+int set_dynamic_lds(const void *kernel, size_t bytes)
+{
+    int dev = -1;
+    SVG2_HIP_CHECK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_lds_mu);
+    for (const LdsAttr &e : g_lds_done)
+        if (e.kernel == kernel && e.device == dev && e.bytes >= bytes) return SVG2_OK;
+    SVG2_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    g_lds_done.push_back({kernel, dev, bytes});
+    return SVG2_OK;
+}
 
 // Layout of svg2_forward's workspace.
 struct ForwardLayout {
@@ -106,10 +121,8 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     L.sk = c.take<float>(fp8 ? (size_t)H : 0);
     L.sv = c.take<float>(fp8 ? (size_t)H : 0);
     // the stages run one after another on one stream and share one scratch area
-    size_t s = kmeans_ws_bytes(dtype, H, N, d, Cq);
-    size_t t = kmeans_ws_bytes(dtype, H, N, d, Ck);
-    if (t > s) s = t;
-    t = permute_ws_bytes(H, N, Cq > Ck ? Cq : Ck);
+    size_t s = kmeans_pair_ws_bytes(dtype, H, N, d, Cq, Ck);     // both sides run in the same launches
+    size_t t = permute_ws_bytes(H, N, Cq) + permute_ws_bytes(H, N, Ck);
     if (t > s) s = t;
     t = select_ws_bytes(H, Cq, Ck);
     if (t > s) s = t;
@@ -178,6 +191,7 @@ int svg2_kmeans(const void *X, int dtype, int H, int N, int d, int C, int iters,
     SVG2_REQUIRE(X && init_centroids && centroids && labels && counts, SVG2_INVALID_ARG,
                  "X, init_centroids, centroids, labels and counts must be non-null");
     SVG2_TRY(check_ws(ws, ws_bytes, kmeans_ws_bytes(dtype, H, N, d, C)));
+    SVG2_TRY(kmeans_prepare(dtype, d));
     return kmeans_launch(X, dtype, H, N, d, C, iters, init_centroids, centroids, labels, counts, objective, ws,
                          static_cast<hipStream_t>(stream));
 }
@@ -258,6 +272,7 @@ int svg2_select_topp(const float *cq, const float *ck, const int32_t *counts_q, 
                  "cq, ck, counts_k, row_ptr and col_idx must be non-null");
     SVG2_REQUIRE(!density || counts_q, SVG2_INVALID_ARG, "density needs counts_q");
     SVG2_TRY(check_ws(ws, ws_bytes, select_ws_bytes(H, Cq, Ck)));
+    SVG2_TRY(select_prepare());
     return select_launch(cq, ck, counts_q, counts_k, H, Cq, Ck, d, top_p, row_ptr, col_idx, p_est, density, ws,
                          static_cast<hipStream_t>(stream));
 }
@@ -283,6 +298,7 @@ int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype, 
                  "Qp, Kp, Vp, O, offsets_q, offsets_k, row_ptr and col_idx must be non-null");
     SVG2_REQUIRE(O != Qp && O != Kp && O != Vp, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(dtype, H, N, d, Cq, Ck)));
+    SVG2_TRY(attn_prepare(dtype, d));
     return attn_launch(Qp, Kp, Vp, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, nullptr,
                        scale, O, lse, ws, static_cast<hipStream_t>(stream));
 }
@@ -301,6 +317,7 @@ int svg2_sparse_attn_gather_free(const void *Q, const void *K, const void *V, in
                  "Q, K, V, O, offsets_q, offsets_k, row_ptr, col_idx, perm_q and perm_k must be non-null");
     SVG2_REQUIRE(O != Q && O != K && O != V, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(dtype, H, N, d, Cq, Ck)));
+    SVG2_TRY(attn_prepare(dtype, d));
     return attn_launch(Q, K, V, dtype, H, N, d, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, perm_q, perm_k, scale,
                        O, lse, ws, static_cast<hipStream_t>(stream));
 }
@@ -357,38 +374,34 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
         lse = aux->lse;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // everything that can fail without a kernel having been launched comes first
+    SVG2_TRY(kmeans_prepare(dtype, d));
+    SVG2_TRY(select_prepare());
+    if (mode == FWD_FP8) SVG2_TRY(attn_fp8_prepare());
+    else SVG2_TRY(attn_prepare(dtype, d));
     const int pb = profile_begin_call();
     profile_mark(pb, 0, st);
-    // Section 4.1: cluster Q and K independently
-    SVG2_TRY(kmeans_launch(Q, dtype, H, N, d, Cq, iters, cq_inout, cq_inout, L.labels_q, L.counts_q, nullptr,
-                           L.stage_ws, st));
+    // Section 4.1: cluster Q and K independently (both sides share every launch)
+    SVG2_TRY(kmeans_pair_launch(Q, K, dtype, H, N, d, Cq, Ck, iters, cq_inout, ck_inout, L.labels_q, L.labels_k,
+                                L.counts_q, L.counts_k, L.stage_ws, st));
     profile_mark(pb, 1, st);
-    SVG2_TRY(kmeans_launch(K, dtype, H, N, d, Ck, iters, ck_inout, ck_inout, L.labels_k, L.counts_k, nullptr,
-                           L.stage_ws, st));
-    profile_mark(pb, 2, st);
     // Section 4.1: permutations; K and V share pi_k
     // (gather-free: only the index vectors; the rows are fetched through them in the attention kernel)
-    const void *src_q[1] = {Q};
-    void *dst_q[1] = {L.Qp};
-    SVG2_TRY(permute_launch(L.labels_q, H, N, Cq, L.offsets_q, L.perm_q, nullptr, gather_free ? 0 : 1, src_q, dst_q,
-                            dtype, d, L.stage_ws, st));
-    const void *src_k[2] = {K, V};
-    void *dst_k[2] = {L.Kp, L.Vp};
-    SVG2_TRY(permute_launch(L.labels_k, H, N, Ck, L.offsets_k, L.perm_k, nullptr, gather_free ? 0 : 2, src_k, dst_k,
-                            dtype, d, L.stage_ws, st));
+    SVG2_TRY(permute_pair_launch(L.labels_q, L.labels_k, H, N, Cq, Ck, L.offsets_q, L.offsets_k, L.perm_q, L.perm_k,
+                                 !gather_free, Q, K, V, L.Qp, L.Kp, L.Vp, dtype, d, L.stage_ws, st));
     if (mode == FWD_FP8) {              // E4M3 copies in token order, one scale per head and tensor
         SVG2_TRY(fp8_quant_launch(Q, dtype, H, N, d, L.Q8, L.sq, L.stage_ws, st));
         SVG2_TRY(fp8_quant_launch(K, dtype, H, N, d, L.K8, L.sk, L.stage_ws, st));
         SVG2_TRY(fp8_quant_launch(V, dtype, H, N, d, L.V8, L.sv, L.stage_ws, st));
     }
-    profile_mark(pb, 3, st);
+    profile_mark(pb, 2, st);
     // Section 4.2: which (query cluster, key cluster) pairs to compute
     SVG2_TRY(select_launch(cq_inout, ck_inout, L.counts_q, L.counts_k, H, Cq, Ck, d, top_p, L.row_ptr, L.col_idx,
                            nullptr, L.density, L.stage_ws, st));
-    profile_mark(pb, 4, st);
+    profile_mark(pb, 3, st);
     // Section 4.3: attention over the selected pairs, result back in token order
     SVG2_TRY(attn_plan_launch(dtype, H, N, Cq, Ck, L.offsets_q, L.offsets_k, L.row_ptr, L.col_idx, L.stage_ws, st));
-    profile_mark(pb, 5, st);
+    profile_mark(pb, 4, st);
     if (mode == FWD_FP8)
         SVG2_TRY(attn_fp8_main_launch(L.Q8, L.K8, L.V8, L.sq, L.sk, L.sv, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, L.perm_k,
                                       0.f, O, lse, L.stage_ws, st));
@@ -398,7 +411,7 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
     else
         SVG2_TRY(attn_main_launch(L.Qp, L.Kp, L.Vp, dtype, H, N, d, Cq, Ck, L.row_ptr, L.perm_q, nullptr, 0.f, O, lse,
                                   L.stage_ws, st));
-    profile_mark(pb, 6, st);
+    profile_mark(pb, 5, st);
     return SVG2_OK;
 }
 
@@ -470,6 +483,7 @@ int svg2_sparse_attn_fp8(const void *Q8, const void *K8, const void *V8, const f
     SVG2_REQUIRE(!perm_k || perm_q, SVG2_INVALID_ARG, "perm_k (operands in token order) needs perm_q");
     SVG2_REQUIRE(O != Q8 && O != K8 && O != V8, SVG2_INVALID_ARG, "O must not alias an input");
     SVG2_TRY(check_ws(ws, ws_bytes, attn_ws_bytes(SVG2_BF16, H, N, d, Cq, Ck)));
+    SVG2_TRY(attn_fp8_prepare());
     hipStream_t st = static_cast<hipStream_t>(stream);
     SVG2_TRY(attn_plan_launch(SVG2_BF16, H, N, Cq, Ck, offsets_q, offsets_k, row_ptr, col_idx, ws, st));
     return attn_fp8_main_launch(Q8, K8, V8, scale_q, scale_k, scale_v, H, N, d, Cq, Ck, row_ptr, perm_q, perm_k, scale,

@@ -26,6 +26,7 @@
 // Gather-free variant (perm_k given): Q, K and V stay in token order and the
 // kernels go through perm_q / perm_k when they fetch a row -- the per-token
 // sparse load of Section 4.3 -- so no permuted copies are needed.
+#include <algorithm>
 #include <type_traits>
 
 #include "svg2_attn_shared.h"
@@ -832,6 +833,26 @@ size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck)
     return attn_carve(nullptr, dtype, H, N, Cq, Ck).bytes;
 }
 
+static size_t attn_lds_bytes(int d, int Ck)
+{
+    return (size_t)2 * ATT_NSTG * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
+           (size_t)std::min(Ck + 1, ATT_RUN_LDS) * sizeof(int2);
+}
+
+int attn_prepare(int dtype, int d)
+{
+    if (dtype != SVG2_BF16) return SVG2_OK;
+    const size_t lds = attn_lds_bytes(d, SVG2_MAX_CLUSTERS);
+    if (d == 128) {
+        SVG2_TRY(set_dynamic_lds(reinterpret_cast<const void *>(attn_bf16_kernel<128, true>), lds));
+        SVG2_TRY(set_dynamic_lds(reinterpret_cast<const void *>(attn_bf16_kernel<128, false>), lds));
+    } else {
+        SVG2_TRY(set_dynamic_lds(reinterpret_cast<const void *>(attn_bf16_kernel<64, true>), lds));
+        SVG2_TRY(set_dynamic_lds(reinterpret_cast<const void *>(attn_bf16_kernel<64, false>), lds));
+    }
+    return SVG2_OK;
+}
+
 int attn_plan_launch(int dtype, int H, int N, int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
                      const int32_t *row_ptr, const int32_t *col_idx, void *ws, hipStream_t st)
 {
@@ -867,13 +888,10 @@ int attn_main_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, 
         const bf16_t *q = static_cast<const bf16_t *>(Qp), *k = static_cast<const bf16_t *>(Kp),
                      *v = static_cast<const bf16_t *>(Vp);
         bf16_t *o = static_cast<bf16_t *>(O);
-        const size_t lds = (size_t)2 * ATT_NSTG * ATT_BN * d * sizeof(bf16_t) + 2 * ATT_BN * sizeof(int32_t) +
-                           (size_t)std::min(Ck + 1, ATT_RUN_LDS) * sizeof(int2);
+        const size_t lds = attn_lds_bytes(d, Ck);
         const bool cap = Ck + 1 > ATT_RUN_LDS;
         auto kern = d == 128 ? (cap ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
                              : (cap ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
-        SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, q, k, v, H, N, Cq, Ck, row_ptr, perm_q, perm_k, tiles,
                            tile_base, a.order, max_tiles, runs, row_keys, a.tile_run, a.key_tiles, scale_log2, group, o, lse);
     } else {

@@ -25,6 +25,17 @@ void clear_error();
             return ::svg2::fail(SVG2_HIP_ERROR, "%s: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
+#define SVG2_TRY(expr)                    \
+    do {                                  \
+        int rc_ = (expr);                 \
+        if (rc_ != SVG2_OK) return rc_;   \
+    } while (0)
+
+// Raises the dynamic-LDS limit of a kernel to `bytes` on the current device (once per kernel and device; later
+// calls with the same or a smaller size return at once).  Called from the *_prepare functions, which run before
+// the first launch of an entry point so that a failure leaves nothing enqueued.
+int set_dynamic_lds(const void *kernel, size_t bytes);
+
 // ---- workspace carving -----------------------------------------------------
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -69,11 +80,41 @@ template <> struct Elem<bf16_t> {
 // All of them assume validated arguments and a workspace of the right size.
 
 size_t kmeans_ws_bytes(int dtype, int H, int N, int d, int C);
+int kmeans_prepare(int dtype, int d);
 int kmeans_launch(const void *X, int dtype, int H, int N, int d, int C, int iters,
                   const float *init, float *centroids, int32_t *labels, int32_t *counts,
                   float *objective, void *ws, hipStream_t st);
+// k-means of the Q tokens and of the K tokens of a layer together (one launch per step for both sides); the
+// workspace holds both sides' scratch (kmeans_pair_ws_bytes)
+size_t kmeans_pair_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck);
+int kmeans_pair_launch(const void *Q, const void *K, int dtype, int H, int N, int d, int Cq, int Ck, int iters,
+                       float *cq_inout, float *ck_inout, int32_t *labels_q, int32_t *labels_k, int32_t *counts_q,
+                       int32_t *counts_k, void *ws, hipStream_t st);
+
+// One problem of the counting sort (all heads of one side: the Q tokens or the K tokens of a layer).
+struct SortSide {
+    const int32_t *labels;      // [H,N] values in [0,C)
+    int C, nbits;               // nbits: bits of a label (set by sort_launch)
+    int32_t *hist;              // [H, ceil(N / 1024), C] scratch
+    int32_t *offsets;           // [H,C+1] out
+    int32_t *perm;              // [H,N] out
+    int32_t *inv_perm;          // [H,N] out or null
+    // optional (k-means update step): pieces of at most seg sorted rows inside one cluster
+    int4 *pieces;               // [H,max_pieces] out or null
+    int32_t *first_piece;       // [H,C+1] out
+    int32_t *n_pieces;          // [H] out
+    int max_pieces, seg;
+};
+struct SortArgs {
+    SortSide s[2];
+};
+int sort_launch(SortArgs a, int nsides, int H, int N, hipStream_t st);
 
 size_t permute_ws_bytes(int H, int N, int C);
+int permute_pair_launch(const int32_t *labels_q, const int32_t *labels_k, int H, int N, int Cq, int Ck,
+                        int32_t *offsets_q, int32_t *offsets_k, int32_t *perm_q, int32_t *perm_k, bool copy,
+                        const void *Q, const void *K, const void *V, void *Qp, void *Kp, void *Vp, int dtype, int d,
+                        void *ws, hipStream_t st);
 int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets, int32_t *perm,
                    int32_t *inv_perm, int n_tensors, const void *const *src, void *const *dst,
                    int dtype, int d, void *ws, hipStream_t st);
@@ -82,11 +123,14 @@ int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets,
 int permute_static_scratch(void **out);
 
 size_t select_ws_bytes(int H, int Cq, int Ck);
+int select_prepare();
 int select_launch(const float *cq, const float *ck, const int32_t *counts_q, const int32_t *counts_k,
                   int H, int Cq, int Ck, int d, float top_p, int32_t *row_ptr, int32_t *col_idx,
                   float *p_est, float *density, void *ws, hipStream_t st);
 
 size_t attn_ws_bytes(int dtype, int H, int N, int d, int Cq, int Ck);
+int attn_prepare(int dtype, int d);
+int attn_fp8_prepare();
 int attn_launch(const void *Qp, const void *Kp, const void *Vp, int dtype, int H, int N, int d,
                 int Cq, int Ck, const int32_t *offsets_q, const int32_t *offsets_k,
                 const int32_t *row_ptr, const int32_t *col_idx, const int32_t *perm_q,

@@ -630,6 +630,16 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     }
 }
 
+static size_t attn_fp8_lds_bytes(int d, int Ck)
+{
+    return (size_t)2 * F8_NSTG * ATT_BN * d + 2 * ATT_BN * sizeof(int32_t) + (size_t)(Ck + 1) * sizeof(int2);
+}
+
+int attn_fp8_prepare()
+{
+    return set_dynamic_lds(reinterpret_cast<const void *>(attn_fp8_kernel<128>), attn_fp8_lds_bytes(128, SVG2_MAX_CLUSTERS));
+}
+
 int attn_fp8_main_launch(const void *Q8, const void *K8, const void *V8, const float *scale_q, const float *scale_k,
                          const float *scale_v, int H, int N, int d, int Cq, int Ck, const int32_t *row_ptr,
                          const int32_t *perm_q, const int32_t *perm_k, float scale, void *O, float *lse, void *ws,
@@ -641,10 +651,8 @@ int attn_fp8_main_launch(const void *Q8, const void *K8, const void *V8, const f
     const int group = ATT_GROUP;
     const int nwg = cdiv(total, 8 * group) * 8 * group;
     const float scale_log2 = scale * 1.4426950408889634f;
-    const size_t lds = (size_t)2 * F8_NSTG * ATT_BN * d + 2 * ATT_BN * sizeof(int32_t) + (size_t)(Ck + 1) * sizeof(int2);
+    const size_t lds = attn_fp8_lds_bytes(d, Ck);
     auto kern = attn_fp8_kernel<128>;
-    SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds));
     hipLaunchKernelGGL(kern, dim3(nwg), dim3(64 * ATT_NW), lds, st, static_cast<const uint8_t *>(Q8),
                        static_cast<const uint8_t *>(K8), static_cast<const uint8_t *>(V8), scale_q, scale_k, scale_v, H,
                        N, Cq, Ck, row_ptr, perm_q, perm_k, a.tiles, a.tile_base, a.order, a.max_tiles, a.runs, a.row_keys,

@@ -249,6 +249,14 @@ size_t select_ws_bytes(int H, int Cq, int Ck)
     return c.used;
 }
 
+static size_t select_lds_bytes(int Ck, int d)
+{
+    return (size_t)next_pow2(Ck) * (sizeof(unsigned long long) + sizeof(float)) + (size_t)d * sizeof(float) +
+           (size_t)Ck * sizeof(int32_t);
+}
+
+int select_prepare() { return set_dynamic_lds(reinterpret_cast<const void *>(select_row_kernel), select_lds_bytes(SVG2_MAX_CLUSTERS, 128)); }
+
 int select_launch(const float *cq, const float *ck, const int32_t *counts_q, const int32_t *counts_k,
                   int H, int Cq, int Ck, int d, float top_p, int32_t *row_ptr, int32_t *col_idx,
                   float *p_est, float *density, void *ws, hipStream_t st)
@@ -258,10 +266,7 @@ int select_launch(const float *cq, const float *ck, const int32_t *counts_q, con
     int32_t *row_len = c.take<int32_t>((size_t)H * Cq);
     int32_t *row_keys = c.take<int32_t>((size_t)H * Cq);
     const int np2 = next_pow2(Ck);
-    const size_t lds = (size_t)np2 * (sizeof(unsigned long long) + sizeof(float)) + (size_t)d * sizeof(float) +
-                       (size_t)Ck * sizeof(int32_t);
-    SVG2_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(select_row_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const size_t lds = select_lds_bytes(Ck, d);
     hipLaunchKernelGGL(select_row_kernel, dim3(Cq, H), dim3(SEL_THREADS), lds, st, cq, ck, counts_q, counts_k, Cq, Ck,
                        d, np2, top_p, p_est, lists, row_len, row_keys);
     hipLaunchKernelGGL(select_compact_kernel, dim3(H), dim3(SEL_THREADS), (size_t)(Cq + 1) * sizeof(int32_t), st,

@@ -3,11 +3,13 @@
 The quantiser is compared bit for bit (codes and scales).  The attention kernel is compared with
 the oracle's block-sparse attention evaluated on the SAME quantised operands (decoded codes, scales
 folded in), so what is left is the kernel's own arithmetic: fp32 scores and softmax, probabilities
-rounded to E4M3 (3 mantissa bits: relative rounding error within 2^-4, about 0.026 rms), fp32
-accumulation, bf16 output.  Tolerances (derived from that):
-  * O:   relative rms error over the checked rows <= 0.036 (the rms of a uniform rounding error of
-         2^-4 half-width; an output is a weighted mean of values with independent errors of that
-         size on the weights), and no element further off than 0.03 max|V| of its head;
+rounded to E4M3 (3 mantissa bits: relative rounding error within 2^-4), fp32 accumulation, bf16
+output.  Tolerances (derived from that, see _util.assert_fp8_attention_within_budget):
+  * O:   EVERY checked element within the budget of a weighted mean whose weights carry a relative
+         error of 2^-4 (an absolute one of 2^-16 of the row sum for the keys far below the row
+         maximum), (2^-4 dev1 + 2^-16 tail1) / (1 - 2^-4 - 2^-16 keys) + 2^-8 |O_ref| + 1e-5, with
+         dev1 = sum_j pi_j |v_jc - O_c| from the oracle; and within 10 standard deviations of what
+         independent rounding errors give, rms of the normalised error at most 1.25;
   * lse: the row sum is the sum of the rounded probabilities, so |lse - ref| <= ln(1 + 2^-4) = 0.0606
          in the worst case, and far less on average (<= 0.01) unless a row's probabilities are all
          nearly equal (then they all round the same way).
@@ -17,11 +19,9 @@ import pytest
 import torch
 
 from paper_2505_18875_amd import workloads as wl
-from _util import head_inputs, to_dev, to_np
+from _util import FP8_LSE_MAX as LSE_MAX, assert_fp8_attention_within_budget, head_inputs, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
-
-O_REL_RMS, O_MAX_FRAC, LSE_MAX, LSE_MEAN = 0.036, 0.03, 0.0606 + 2e-3, 0.01
 
 
 @pytest.fixture(scope="module")
@@ -72,26 +72,22 @@ def test_quantize_fp8_ties_signs_zero_heads(svg2, oracle):
     assert float(scale[0]) == 1.0 and float(scale[1]) == 1.0 and not X8[1].any()
 
 
-def _oracle_on_quantised(oracle, Q, K, V, a, i, d, rows):
-    """Oracle attention of head i on the decoded E4M3 operands; returns (O, lse) indexed by token."""
-    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
-    pq, pk = to_np(a.perm_q[i]), to_np(a.perm_k[i])
-    rp, ci = to_np(a.row_ptr[i]), to_np(a.col_idx[i])
-    sc = (1.0 / np.sqrt(d)) * float(dq[2]) * float(dk[2])
-    O, lse = oracle.sparse_attention(dq[1][pq], dk[1][pk], dv[1][pk], to_np(a.offsets_q[i]), to_np(a.offsets_k[i]),
-                                     rp, ci[: rp[-1]], perm_q=pq, scale=sc, rows=rows)
-    return O * float(dv[2]), lse, pq
+def _check_head(oracle, O, lse, Q, K, V, d, perm_q, perm_k, offsets_q, offsets_k, row_ptr, col_idx, rows=None,
+                lse_mean=None, statistical=True, what=""):
+    """One head of the kernel's output against the oracle on the decoded E4M3 operands, element by element."""
+    (_, dq, sq), (_, dk, sk), (_, dv, sv) = (oracle.quantize_e4m3(x) for x in (Q, K, V))
+    kw = dict(statistical=statistical)
+    if lse_mean is not None:
+        kw["lse_mean"] = lse_mean
+    return assert_fp8_attention_within_budget(oracle, np.asarray(O, np.float64), np.asarray(lse, np.float64), dq, dk, dv,
+                                              sq, sk, sv, d, perm_q, perm_k, offsets_q, offsets_k, row_ptr, col_idx,
+                                              rows=rows, what=what, **kw)
 
 
-def _check_against(O, lse, O_ref, lse_ref, tok, vmax, lse_mean=LSE_MEAN):
-    err = O[tok] - O_ref[tok]
-    rel = np.sqrt((err ** 2).mean() / max((O_ref[tok] ** 2).mean(), 1e-30))
-    assert rel <= O_REL_RMS, rel
-    assert np.abs(err).max() <= O_MAX_FRAC * vmax, (np.abs(err).max(), vmax)
-    fin = np.isfinite(lse_ref[tok])
-    dl = np.abs(lse[tok][fin] - lse_ref[tok][fin])
-    assert dl.max() <= LSE_MAX and dl.mean() <= lse_mean, (dl.max(), dl.mean())
-    assert np.all(np.isneginf(lse[tok][~fin]))
+def _check_aux_head(oracle, res_O, lse, Q, K, V, a, i, d, rows, what=""):
+    return _check_head(oracle, to_np(res_O[i]), to_np(lse[i]), Q, K, V, d, to_np(a.perm_q[i]), to_np(a.perm_k[i]),
+                       to_np(a.offsets_q[i]), to_np(a.offsets_k[i]), to_np(a.row_ptr[i]), to_np(a.col_idx[i]),
+                       rows=rows, what=what)
 
 
 @pytest.mark.parametrize("heads,top_p", [([2, 19], 0.9), ([7], 0.5)])
@@ -106,9 +102,7 @@ def test_sparse_attn_fp8_matches_oracle_on_the_quantised_operands(svg2, oracle, 
     torch.cuda.synchronize()
     for i, h in enumerate(heads):
         rows = np.sort(np.random.default_rng(h).choice(w.N, 512, replace=False)).astype(np.int32)
-        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, Q[i], K[i], V[i], a, i, w.d, rows)
-        _check_against(to_np(res.O[i]).astype(np.float64), to_np(res.lse[i]).astype(np.float64), O_ref, lse_ref,
-                       pq[rows], np.abs(V[i]).max())
+        _check_aux_head(oracle, res.O, res.lse, Q[i], K[i], V[i], a, i, w.d, rows, what="head %d" % h)
     # the operands as permuted copies (perm_k = None): same rows in the same order, same bits
     def gather(X8, perm):
         return torch.gather(X8, 1, perm.long()[:, :, None].expand(-1, -1, X8.shape[2])).contiguous()
@@ -145,13 +139,8 @@ def test_sparse_attn_fp8_ragged_and_empty_clusters(svg2, oracle):
                                     to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
                                     to_dev(pk.perm[None]), want_lse=True)
     torch.cuda.synchronize()
-    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
-    O_ref, lse_ref = oracle.sparse_attention(dq[1][pq.perm], dk[1][pk.perm], dv[1][pk.perm], pq.offsets, pk.offsets,
-                                             row_ptr, cat, perm_q=pq.perm,
-                                             scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
-    O_ref *= float(dv[2])
     O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
-    _check_against(O, lse, O_ref, lse_ref, np.arange(N), np.abs(V).max())
+    _check_head(oracle, O, lse, Q, K, V, d, pq.perm, pk.perm, pq.offsets, pk.offsets, row_ptr, col)
     for i in (1, 2):
         rows = np.nonzero(lq == i)[0]
         assert rows.size and np.all(O[rows] == 0.0) and np.all(np.isneginf(lse[rows]))
@@ -178,15 +167,9 @@ def test_sparse_attn_fp8_thousands_of_short_key_clusters(svg2, oracle):
                                     to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
                                     to_dev(pk.perm[None]), want_lse=True)
     torch.cuda.synchronize()
-    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
-    O_ref, lse_ref = oracle.sparse_attention(dq[1][pq.perm], dk[1][pk.perm], dv[1][pk.perm], pq.offsets, pk.offsets,
-                                             row_ptr, cat, perm_q=pq.perm,
-                                             scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
-    O_ref *= float(dv[2])
     O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
-    fin = np.isfinite(lse_ref)                                  # a query cluster whose 3 key clusters are all empty has no keys
-    _check_against(O[fin], lse[fin], O_ref[fin], lse_ref[fin], np.arange(int(fin.sum())), np.abs(V).max())
-    assert np.all(O[~fin] == 0.0) and np.all(np.isneginf(lse[~fin]))
+    # (a query cluster whose 3 key clusters are all empty has no keys: the check wants O = 0, lse = -inf there)
+    _check_head(oracle, O, lse, Q, K, V, d, pq.perm, pk.perm, pq.offsets, pk.offsets, row_ptr, col)
 
 
 def test_sparse_attn_fp8_dense_special_case_flat_and_peaked_rows(svg2, oracle):
@@ -204,15 +187,17 @@ def test_sparse_attn_fp8_dense_special_case_flat_and_peaked_rows(svg2, oracle):
     res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, one, one, to_dev(np.array([[0, 1]], dtype=np.int32)),
                                     to_dev(np.zeros((1, 1), dtype=np.int32)), None, None, want_lse=True)
     torch.cuda.synchronize()
-    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
-    O_ref, lse_ref = oracle.dense_attention(dq[1], dk[1], dv[1], scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
-    O_ref = O_ref * float(dv[2])
     O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    ident = np.arange(N, dtype=np.int32)
+    off = np.array([0, N], dtype=np.int32)
+    rp1, ci1 = np.array([0, 1], dtype=np.int32), np.zeros(1, dtype=np.int32)
     # flat rows: all probabilities of a row are nearly the same number and round the same way, so the error of
     # the row sum does not average out -- only the worst-case bound holds for lse (the output is a ratio of two
     # sums with that common factor and keeps its accuracy)
-    _check_against(O, lse, O_ref, lse_ref, np.arange(N // 2), np.abs(V).max(), lse_mean=LSE_MAX)
-    _check_against(O, lse, O_ref, lse_ref, np.arange(N // 2, N), np.abs(V).max())
+    _check_head(oracle, O, lse, Q, K, V, d, ident, ident, off, off, rp1, ci1, rows=np.arange(N // 2, dtype=np.int32),
+                lse_mean=LSE_MAX, statistical=False, what="flat rows")
+    _check_head(oracle, O, lse, Q, K, V, d, ident, ident, off, off, rp1, ci1,
+                rows=np.arange(N // 2, N, dtype=np.int32), what="peaked rows")
 
 
 def test_forward_fp8_same_selection_as_forward_and_close_output(svg2, oracle):
@@ -239,9 +224,7 @@ def test_forward_fp8_same_selection_as_forward_and_close_output(svg2, oracle):
     # against the oracle on the quantised operands
     for i, h in enumerate(heads):
         rows = np.sort(np.random.default_rng(h).choice(w.N, 256, replace=False)).astype(np.int32)
-        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, Q[i], K[i], V[i], a, i, w.d, rows)
-        _check_against(to_np(res.O[i]).astype(np.float64), to_np(a.lse[i]).astype(np.float64), O_ref, lse_ref,
-                       pq[rows], np.abs(V[i]).max())
+        _check_aux_head(oracle, res.O, a.lse, Q[i], K[i], V[i], a, i, w.d, rows, what="head %d" % h)
 
 
 def test_fp8_entry_points_reject_what_they_do_not_support(svg2):
@@ -290,12 +273,12 @@ def test_forward_fp8_wan_like_full_size(svg2, oracle):
     for n in ("labels_q", "labels_k", "perm_q", "perm_k", "row_ptr", "density"):
         assert torch.equal(getattr(a, n), getattr(ref.aux, n)), n
     assert bool(torch.isfinite(res.O.float()).all())
-    for h in (0, 39):
+    for h in (0, 19, 39):
         q, k, v = to_np(Q[h]), to_np(K[h]), to_np(V[h])
-        rows = np.sort(np.random.default_rng(h).choice(w.N, 128, replace=False)).astype(np.int32)
-        O_ref, lse_ref, pq = _oracle_on_quantised(oracle, q, k, v, a, h, w.d, rows)
-        _check_against(to_np(res.O[h]).astype(np.float64), to_np(a.lse[h]).astype(np.float64), O_ref, lse_ref,
-                       pq[rows], np.abs(v).max())
+        rows = np.sort(np.random.default_rng(h).choice(w.N, 192, replace=False)).astype(np.int32)
+        m = _check_aux_head(oracle, res.O, a.lse, q, k, v, a, h, w.d, rows, what="wan-like head %d" % h)
+        print("wan-like head %d, E4M3: worst |err| / bound %.3f  max z %.2f  rms z %.3f" % (
+            h, m["worst"], m["z_max"], m["z_rms"]), flush=True)
     # against the bf16 layer on the same selection: the operands' rounding, a loose sanity bound
     d = (res.O.float() - ref.O.float())
     rel = (d.pow(2).sum((1, 2)) / ref.O.float().pow(2).sum((1, 2))).sqrt()
@@ -314,9 +297,9 @@ def test_sparse_attn_fp8_very_short_sequences(svg2, oracle, N):
     res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, one, one, to_dev(np.array([[0, 1]], dtype=np.int32)),
                                     to_dev(np.zeros((1, 1), dtype=np.int32)), None, None, want_lse=True)
     torch.cuda.synchronize()
-    dq, dk, dv = oracle.quantize_e4m3(Q), oracle.quantize_e4m3(K), oracle.quantize_e4m3(V)
-    O_ref, lse_ref = oracle.dense_attention(dq[1], dk[1], dv[1], scale=float(dq[2]) * float(dk[2]) / np.sqrt(d))
-    O_ref = O_ref * float(dv[2])
     O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
-    assert np.abs(O - O_ref).max() <= O_MAX_FRAC * np.abs(V).max() + 1e-2
-    assert np.abs(lse - lse_ref).max() <= LSE_MAX
+    ident = np.arange(N, dtype=np.int32)
+    off = np.array([0, N], dtype=np.int32)
+    # with a handful of keys the rounding errors of a row do not average out: only the worst-case figures apply
+    _check_head(oracle, O, lse, Q, K, V, d, ident, ident, off, off, np.array([0, 1], dtype=np.int32),
+                np.zeros(1, dtype=np.int32), lse_mean=LSE_MAX, statistical=False)

@@ -14,7 +14,7 @@ import pytest
 import torch
 
 from paper_2505_18875_amd import workloads as wl
-from _util import assert_label_disagreements_are_near_ties, head_inputs, to_dev, to_np
+from _util import assert_csr_matches, assert_label_disagreements_are_near_ties, check_layer_head, head_inputs, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -69,21 +69,11 @@ def _check_select(oracle, res, cq, ck, counts_q, counts_k, p, H):
     n_low_margin = 0
     for h in range(H):
         ref = oracle.select_topp(cq[h], ck[h], None if counts_q is None else counts_q[h], counts_k[h], p)
-        got_ptr, got_col = to_np(res.row_ptr[h]), to_np(res.col_idx[h])
-        got_rows, ref_rows = _csr_rows(got_ptr, got_col), _csr_rows(ref.row_ptr, ref.col_idx)
-        assert got_ptr[0] == 0
-        for i, (g, e) in enumerate(zip(got_rows, ref_rows)):
-            if ref.margin[i] > 1e-5:
-                np.testing.assert_array_equal(g, e, err_msg="head %d row %d" % (h, i))
-            else:
-                n_low_margin += 1
-                # a near-tie at the stopping point: the lists may differ by boundary clusters only
-                diff = set(g.tolist()) ^ set(e.tolist())
-                assert len(diff) <= 2, (h, i, diff)
-                assert np.all(np.diff(g) > 0)
+        low, ndiff = assert_csr_matches(ref, to_np(res.row_ptr[h]), to_np(res.col_idx[h]), "head %d" % h)
+        n_low_margin += ndiff
         if res.p_est is not None:
             np.testing.assert_allclose(to_np(res.p_est[h]), ref.p_est, rtol=2e-4, atol=1e-7)
-        if counts_q is not None and n_low_margin == 0:
+        if counts_q is not None and ndiff == 0:
             np.testing.assert_allclose(float(res.density[h]), ref.density, rtol=1e-5)
     return n_low_margin
 
@@ -205,8 +195,8 @@ def test_kmeans_empty_cluster_keeps_centroid_and_warm_start(svg2, oracle):
 
 @pytest.mark.parametrize("dtype,N,C,iters", [("bf16", 16384, 200, 26), ("f32", 3000, 400, 19)])
 def test_kmeans_many_iterations_centroids_are_means_of_the_labels(svg2, dtype, N, C, iters):
-    # From the third iteration on the update step only moves the tokens whose label changed between the cluster
-    # sums (with a full re-summation every 8th iteration).  Whatever the route, the returned centroids are the means
+    # From the second iteration on the update step only moves the tokens whose label changed between the cluster
+    # sums (with a full re-summation every 16th iteration).  Whatever the route, the returned centroids are the means
     # of the returned labels (reading R2): checked against float64 means of the GPU's own labels, far tighter than
     # the 1e-3 of the oracle comparison, over enough iterations to cross several re-summations; with C close to N
     # some clusters run empty on the way and must keep a centroid without disturbing the sums of the others.
@@ -237,8 +227,11 @@ def test_kmeans_many_iterations_centroids_are_means_of_the_labels(svg2, dtype, N
 
 # ------------------------------------------------------------------ sparse attention
 
-def _attn_case(oracle, svg2, Q, K, V, lq, lk, sel_rows, dtype, rows=None, tol=(2e-2, 1e-3)):
-    """One head.  lq/lk: labels; sel_rows: list of selected key clusters per query cluster."""
+def _attn_case(oracle, svg2, Q, K, V, lq, lk, sel_rows, dtype, rows=None, tol=(2e-2, 1e-3), few_keys=False):
+    """One head.  lq/lk: labels; sel_rows: list of selected key clusters per query cluster.
+    few_keys: the rows attend over a handful of keys, so the outputs are O(1) instead of O(1 / sqrt(keys)) as on
+    the workloads the mean-abs bar of 1e-3 was set for; the bf16 storage of the output alone is then up to
+    2^-9 |O| per element, and the mean bar becomes 1e-3 + 2^-9 mean|O_ref| (the max bar stays)."""
     N, d = Q.shape
     Cq, Ck = len(sel_rows), int(lk.max()) + 1 if lk.size else 1
     Ck = max(Ck, max((int(s.max()) + 1 for s in sel_rows if len(s)), default=1))
@@ -257,7 +250,8 @@ def _attn_case(oracle, svg2, Q, K, V, lq, lk, sel_rows, dtype, rows=None, tol=(2
     lse = to_np(res.lse[0]).astype(np.float64)
     chk = np.arange(N) if rows is None else pq.perm[rows]
     err = np.abs(O[chk] - O_ref[chk])
-    assert err.max() <= tol[0] and err.mean() <= tol[1], (err.max(), err.mean())
+    mean_bar = tol[1] + (2.0 ** -9 * np.abs(O_ref[chk]).mean() if few_keys else 0.0)
+    assert err.max() <= tol[0] and err.mean() <= mean_bar, (err.max(), err.mean(), mean_bar)
     fin = np.isfinite(lse_ref[chk])
     np.testing.assert_allclose(lse[chk][fin], lse_ref[chk][fin], rtol=1e-3, atol=2e-3)
     assert np.all(np.isneginf(lse[chk][~fin]))
@@ -320,10 +314,7 @@ def test_attention_tile_loop_edges_random_small_shapes(svg2, oracle, d):
         if case % 3 == 0:
             lk[: N // 2] = 0                                # one long run, the others short
         sel = [np.sort(r.choice(Ck, size=int(r.integers(0, Ck + 1)), replace=False)) for _ in range(Cq)]
-        # With a handful of keys per row the outputs are O(1), not O(1 / sqrt(keys)) as on the workloads the
-        # mean-abs bar of 1e-3 was set for: the bf16 rounding of the stored output alone (2^-9 relative) is up to
-        # 2e-3 per element, so the mean bar is widened to 4e-3 here; the max bar stays.
-        _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", tol=(2e-2, 4e-3))
+        _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", few_keys=True)
 
 
 def test_attention_more_selected_key_clusters_than_the_run_table_in_lds_holds(svg2, oracle):
@@ -337,7 +328,7 @@ def test_attention_more_selected_key_clusters_than_the_run_table_in_lds_holds(sv
     lk = r.integers(0, Ck, size=N).astype(np.int32)
     sel = [np.sort(r.choice(Ck, size=2600, replace=False)), np.sort(r.choice(Ck, size=1500, replace=False)),
            np.array([5, 900, 2699], dtype=np.int64)]
-    _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", tol=(2e-2, 4e-3))
+    _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, "bf16", few_keys=True)
 
 
 def test_attention_dense_special_case_matches_dense_oracle(svg2, oracle):
@@ -373,46 +364,14 @@ def test_attention_small_bf16_given_oracle_blocks(svg2, oracle):
 def _check_forward(oracle, svg2, w, heads, sample_rows=None):
     bf16 = w.dtype == "bf16"
     Q, K, V, cq, ck = head_inputs(w, heads)
+    Qd, Kd = to_dev(Q, w.dtype), to_dev(K, w.dtype)
     cq_d, ck_d = to_dev(cq), to_dev(ck)
-    res = svg2.svg2_forward(to_dev(Q, w.dtype), to_dev(K, w.dtype), to_dev(V, w.dtype), cq_d, ck_d,
-                            w.top_p, w.iters, want_aux=True)
+    res = svg2.svg2_forward(Qd, Kd, to_dev(V, w.dtype), cq_d, ck_d, w.top_p, w.iters, want_aux=True)
     torch.cuda.synchronize()
-    a = res.aux
-    low_margin = 0
     for i, h in enumerate(heads):
-        ref = oracle.forward(Q[i], K[i], V[i], cq[i], ck[i], w.iters, w.top_p, bf16,
-                             rows=np.zeros(0, dtype=np.int32))
-        # k-means: labels close to the oracle's
-        for got, want in ((a.labels_q[i], ref.kq.labels), (a.labels_k[i], ref.kk.labels)):
-            assert np.mean(to_np(got) == want) >= 0.999
-        # downstream stages judged on the GPU's own upstream results
-        lq, lk = to_np(a.labels_q[i]), to_np(a.labels_k[i])
-        pq, pk = oracle.permute(lq, w.Cq), oracle.permute(lk, w.Ck)
-        np.testing.assert_array_equal(to_np(a.offsets_q[i]), pq.offsets)
-        np.testing.assert_array_equal(to_np(a.offsets_k[i]), pk.offsets)
-        np.testing.assert_array_equal(to_np(a.perm_q[i]), pq.perm)
-        np.testing.assert_array_equal(to_np(a.perm_k[i]), pk.perm)
-        np.testing.assert_array_equal(to_np(a.counts_q[i]), pq.counts)
-        np.testing.assert_array_equal(to_np(a.counts_k[i]), pk.counts)
-        sel = oracle.select_topp(to_np(cq_d[i]), to_np(ck_d[i]), pq.counts, pk.counts, w.top_p)
-        rp, ci = to_np(a.row_ptr[i]), to_np(a.col_idx[i])
-        for r_, (g, e) in enumerate(zip(_csr_rows(rp, ci), _csr_rows(sel.row_ptr, sel.col_idx))):
-            if sel.margin[r_] > 1e-5:
-                np.testing.assert_array_equal(g, e)
-            else:
-                low_margin += 1
-        rows = None if sample_rows is None else np.sort(
-            np.random.default_rng(h).choice(w.N, sample_rows, replace=False)).astype(np.int32)
-        O_ref, _ = oracle.sparse_attention(Q[i][pq.perm], K[i][pk.perm], V[i][pk.perm], pq.offsets, pk.offsets,
-                                           rp, ci[: rp[-1]], perm_q=pq.perm, rows=rows)
-        chk = np.arange(w.N) if rows is None else pq.perm[rows]
-        err = np.abs(to_np(res.O[i])[chk] - O_ref[chk])
-        tol = (2e-2, 1e-3) if bf16 else (1e-4, 1e-5)
-        assert err.max() <= tol[0] and err.mean() <= tol[1], (h, err.max(), err.mean())
-        dens = (pq.counts[:, None] * 0).sum()  # placeholder to keep flake quiet
-        keys = np.array([pk.counts[c].sum() for c in _csr_rows(rp, ci)])
-        np.testing.assert_allclose(float(a.density[i]), (pq.counts * keys).sum() / float(w.N) ** 2, rtol=1e-5)
-    assert low_margin <= max(2, len(heads) * w.Cq // 20)
+        check_layer_head(svg2, oracle, w, Q[i], K[i], V[i], cq[i], ck[i], w.iters, w.top_p, res.aux, i, res.O[i],
+                         cq_d[i], ck_d[i], Qd[i:i + 1], Kd[i:i + 1], n_rows=sample_rows, seed=h,
+                         tol=(2e-2, 1e-3) if bf16 else (1e-4, 1e-5), labels_exact=bf16)
 
 
 def test_attention_many_heads_work_order_fallback(svg2, oracle):

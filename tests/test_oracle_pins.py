@@ -649,7 +649,7 @@ def test_rounded_weights_budget_bounds_every_perturbation_and_is_attained(oracle
     # the adversarial one (every weight pushed towards the side of its value) comes within 1 / (1 + eps) of it.
     r, Q, K, V, lq, lk, sel, pq, args = _budget_case(oracle, 31)
     eps, d = 2.0 ** -4, Q.shape[1]
-    dev1, dev2, _, _ = oracle.rounded_weights_budget(*args, perm_q=pq.perm)
+    dev1, dev2, _, _, _ = oracle.rounded_weights_budget(*args, perm_q=pq.perm)
     O, _ = oracle.sparse_attention(*args, perm_q=pq.perm)
     for n in range(0, Q.shape[0], 7):
         keys = np.nonzero(np.isin(lk, sel[lq[n]]))[0]
@@ -680,25 +680,43 @@ def test_rounded_weights_budget_closed_forms_and_tail(oracle):
     V = np.array([[1.0, -2.0, 0.5, 0.0], [3.0, 2.0, 0.5, 0.0]], np.float32)
     one = np.array([0, 1], np.int32)
     two = np.array([0, 2], np.int32)
-    dev1, dev2, t1, t2 = oracle.rounded_weights_budget(Q, K, V, one, two, one, np.zeros(1, np.int32), tail_ratio=0.5)
+    dev1, dev2, t1, t2, tw = oracle.rounded_weights_budget(Q, K, V, one, two, one, np.zeros(1, np.int32),
+                                                           tail_ratio=0.5, tail_abs=0.1)
     a, diff = 0.75, np.abs(V[0] - V[1]).astype(np.float64)         # ln 3 is stored as float32: a = 3/4 to ~1e-8
     np.testing.assert_allclose(dev1[0], 2 * a * (1 - a) * diff, rtol=1e-7)
     np.testing.assert_allclose(dev2[0], 2 * (a * (1 - a)) ** 2 * diff ** 2, rtol=1e-7)
     # the second key has a third of the largest probability: it is the tail at ratio 0.5; its |v - O| = a |x - y|
-    np.testing.assert_allclose(t1[0], a * diff, rtol=1e-7)
-    np.testing.assert_allclose(t2[0], (a * diff) ** 2, rtol=1e-7)
+    # and its absolute weight error is min(1/4, 0.1 * 3/4) = 0.075
+    np.testing.assert_allclose(t1[0], 0.075 * a * diff, rtol=1e-7)
+    np.testing.assert_allclose(t2[0], (0.075 * a * diff) ** 2, rtol=1e-7)
+    np.testing.assert_allclose(tw[0], 0.075, rtol=1e-7)
+    # a weight cannot lose more than itself: with a huge absolute figure the error is capped at pi_j = 1/4
+    _, _, t1, _, tw = oracle.rounded_weights_budget(Q, K, V, one, two, one, np.zeros(1, np.int32), tail_ratio=0.5,
+                                                    tail_abs=10.0)
+    np.testing.assert_allclose(tw[0], 0.25, rtol=1e-7)
+    np.testing.assert_allclose(t1[0], 0.25 * a * diff, rtol=1e-7)
     # a weighted mean of equal values cannot be wrong whatever the weights: column 2 and 3 have no budget at all
     assert dev1[0, 2] == 0.0 and dev1[0, 3] == 0.0 and t1[0, 3] == 0.0
     # tail sums by brute force against library softmax; sampled rows leave the others untouched
     r, Q, K, V, lq, lk, sel, pq, args = _budget_case(oracle, 32)
     rows = np.array([1, 40, 77], dtype=np.int32)
-    _, _, t1, t2 = oracle.rounded_weights_budget(*args, perm_q=pq.perm, rows=rows, tail_ratio=0.05)
+    _, _, t1, t2, tw = oracle.rounded_weights_budget(*args, perm_q=pq.perm, rows=rows, tail_ratio=0.05, tail_abs=0.01)
     O, _ = oracle.sparse_attention(*args, perm_q=pq.perm)
     for n in pq.perm[rows]:
         keys = np.nonzero(np.isin(lk, sel[lq[n]]))[0]
         pi = scipy.special.softmax(K[keys].astype(np.float64) @ Q[n].astype(np.float64) / np.sqrt(Q.shape[1]))
         tail = pi < 0.05 * pi.max()
+        a = np.minimum(pi[tail], 0.01 * pi.max())
         dv = np.abs(V[keys][tail].astype(np.float64) - O[n])
-        np.testing.assert_allclose(t1[n], dv.sum(axis=0), rtol=1e-10, atol=1e-14)
-        np.testing.assert_allclose(t2[n], (dv ** 2).sum(axis=0), rtol=1e-10, atol=1e-14)
+        np.testing.assert_allclose(t1[n], (a[:, None] * dv).sum(axis=0), rtol=1e-10, atol=1e-16)
+        np.testing.assert_allclose(t2[n], ((a[:, None] * dv) ** 2).sum(axis=0), rtol=1e-10, atol=1e-18)
+        np.testing.assert_allclose(tw[n], a.sum(), rtol=1e-10, atol=1e-16)
+        # absolute errors within a_j on the tail keys, relative ones within eps on all: inside the combined bound
+        eps = 2.0 ** -4
+        dev1 = (pi[:, None] * np.abs(V[keys].astype(np.float64) - O[n])).sum(axis=0)
+        for trial in range(20):
+            w = pi * (1 + r.uniform(-eps, eps, size=pi.size))
+            w[tail] += r.uniform(-1, 1, size=int(tail.sum())) * a
+            err = (w @ V[keys].astype(np.float64)) / w.sum() - O[n]
+            assert np.all(np.abs(err) <= (eps * dev1 + t1[n]) / (1 - eps - tw[n]) + 1e-15)
     assert np.isnan(np.delete(t1, pq.perm[rows], axis=0)).all()
