@@ -31,10 +31,14 @@ from paper_2505_18875_amd import workloads as wl  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 MFMA peak
 FP8_MFMA_PEAK_TFLOPS = 5000.0           # MI355X dense fp8 MFMA peak
-# HBM-side bytes per attention-kernel launch on the Wan-like layer at top-p 0.9, from two
-# rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy in the
-# same runs): profiles/wan_like_attention_hbm_traffic.md.  Other workloads report null.
+HBM_PEAK_GBPS = 8000.0                  # MI355X HBM3E peak
+# Bytes per attention-kernel launch that leave the L2s towards the fabric (Infinity Cache / HBM) on the Wan-like
+# layer at top-p 0.9, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy
+# in the same runs): profiles/wan_like_attention_hbm_traffic.md.  A constant from that profile, not measured by
+# this script (counters need the profiler); other workloads report null.
 ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 17320346.2 + 1034588.3) * 1024.0}
+ATTN_TRAFFIC_SOURCE = ("fabric-side bytes (L2 misses, FETCH_SIZE / WRITE_SIZE), part of which the Infinity Cache serves; "
+                       "constant from profiles/wan_like_attention_hbm_traffic.md, not measured in this run")
 
 
 def _gen_head(args):
@@ -202,6 +206,21 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     stage_ms = {k: v / n_calls for k, v in stage_ms.items()}
 
+    # a short second pass with an event pair around every kernel of k-means and of the permutation: which kernel
+    # takes what (these events sit between kernels that otherwise run back to back, so this pass is not the timing)
+    kernel_ms = {}
+    if not args.fp8:
+        n_kp = 3
+        svg2.svg2_profile_enable(2)
+        for i in range(n_kp):
+            cqs[i].copy_(cq0)
+            cks[i].copy_(ck0)
+            step(i)
+        torch.cuda.synchronize()
+        svg2.svg2_profile_enable(0)
+        svg2.svg2_profile_read()
+        kernel_ms = {k: (ms / n_kp, cnt // n_kp) for k, (ms, cnt) in svg2.svg2_profile_read_kernels().items()}
+
     dense_flops = 4.0 * H * float(N) ** 2 * d
     sel_flops = dense_flops * float(density.mean())            # 4 d sum_sel |Q_i||K_j| over all heads
     attn_ms = stage_ms["attn"]
@@ -224,8 +243,50 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": None if args.fp8 or w.iters != wl.WORKLOADS[w.name].iters
                      else ATTN_TRAFFIC_BYTES.get((w.name, w.top_p)),
+                     "traffic_source": ATTN_TRAFFIC_SOURCE,
                      "flops_per_launch": sel_flops, "ms_per_launch": attn_ms},
     }
+    if kernel_ms:
+        tensor_bytes = float(H) * N * d * 2                     # one [H,N,d] bf16 tensor
+        rk = []
+
+        def add(name, key, bound=None, flops=None, nbytes=None, note=None):
+            ms, launches = kernel_ms[key]
+            if launches == 0:
+                return
+            e = {"kernel": name, "launches_per_layer": launches, "ms_per_launch": ms / launches, "ms_per_layer": ms}
+            t = ms / launches * 1e-3
+            if flops is not None:
+                e["tflops"] = flops / t / 1e12
+            if nbytes is not None:
+                e["gbps"] = nbytes / t / 1e9
+            if bound == "mfma":
+                e.update(bound="mfma", achieved=e["tflops"], peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                         frac=e["tflops"] / BF16_MFMA_PEAK_TFLOPS)
+            elif bound == "hbm":
+                e.update(bound="hbm", achieved=e["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s", frac=e["gbps"] / HBM_PEAK_GBPS)
+            if note:
+                e["note"] = note
+            rk.append(e)
+
+        # a1: 2 N C d flops per head and side; both sides read their tokens once
+        add("kmeans_assign_bf16_kernel (Q side C=%d and K side C=%d in one launch)" % (w.Cq, w.Ck), "kmeans_assign",
+            bound="mfma", flops=2.0 * N * (w.Cq + w.Ck) * d * H, nbytes=2 * tensor_bytes,
+            note="the K side is matrix-bound, the Q side memory-bound; gbps = Q and K read once")
+        add("kmeans_settle_kernel (near-ties in double precision)", "kmeans_settle")
+        add("permute_hist/scan/scatter_kernel inside k-means (Q and K)", "kmeans_sort")
+        # a2: the first iteration sums every token (both sides read once), the others only the tokens that moved
+        add("kmeans_segsum_kernel, all tokens (Q and K)", "kmeans_segsum_full", bound="hbm", nbytes=2 * tensor_bytes)
+        add("kmeans_segsum_kernel, moved tokens only (Q and K)", "kmeans_segsum_delta")
+        add("kmeans_finalize_kernel (Q and K)", "kmeans_finalize")
+        add("permute_hist/scan/scatter_kernel (pi_q, pi_k)", "permute_sort")
+        # a4: Q', K', V' = three tensors read and written once (two launches: Q, then K and V)
+        if kernel_ms["permute_gather"][1]:
+            ms, _ = kernel_ms["permute_gather"]
+            rk.append({"kernel": "permute_gather_kernel (Q; K and V)", "launches_per_layer": 2, "ms_per_layer": ms,
+                       "bound": "hbm", "achieved": 6 * tensor_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                       "unit": "GB/s", "frac": 6 * tensor_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+        out["roofline_kernels"] = rk
 
     if not args.no_dense:
         # dense attention at the same shape: the same kernel with one query cluster, one key cluster, all selected
@@ -243,7 +304,8 @@ def main():
         dense_ms = e0.elapsed_time(e1)
         out["dense"] = {"ms": dense_ms, "tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
                         "speedup_of_sparse_layer": dense_ms / ms_per_step,
-                        "density_bound_speedup": 1.0 / float(density.mean())}
+                        "density_bound_speedup": 1.0 / float(density.mean()),
+                        "layer_ms_over_density_x_dense_ms": ms_per_step / (float(density.mean()) * dense_ms)}
         log("dense attention, same shape: %.1f ms" % dense_ms)
 
     if not args.no_cpu_baseline:

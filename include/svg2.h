@@ -324,22 +324,42 @@ int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C,
                         void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
- * Stage timing for benchmarks (HOST-side state, one per process).
- * svg2_profile_enable(1): every later svg2_forward call records HIP events
+ * Timing for benchmarks (HOST-side state, one per process).
+ * svg2_profile_enable(1): every later svg2_forward* call records HIP events
  * around its stages on the caller's stream (events are created on first use;
  * at most SVG2_PROFILE_MAX_CALLS calls are kept, later ones go unrecorded).
+ * svg2_profile_enable(2): additionally an event pair around every kernel launch
+ * of k-means and of the permutation (also inside svg2_kmeans / svg2_permute),
+ * at most SVG2_PROFILE_MAX_SPANS of them; these events sit between kernels
+ * that otherwise run back to back, so level 2 is for attributing time to
+ * kernels, not for timing the layer.  svg2_profile_enable(0) stops recording.
  * svg2_profile_read waits for the recorded events, writes the summed
  * milliseconds per stage to stage_ms (HOST array of SVG2_N_STAGES floats, in
  * the order k-means of Q and K (both sides share their launches), permutation
  * Q+K (svg2_forward_fp8: plus the E4M3 quantisation of Q, K, V), selection,
  * attention plan, attention kernel) and the number of recorded calls to
- * n_calls (HOST), then clears the record.  svg2_profile_enable(0) stops
- * recording.
+ * n_calls (HOST), then clears the record.
+ * svg2_profile_read_kernels does the same per kernel class (HOST arrays of
+ * SVG2_N_KERNEL_CLASSES floats / ints: summed milliseconds, launches), in the
+ * order of the SVG2_K_* constants.
  * ------------------------------------------------------------------------- */
 #define SVG2_N_STAGES 5
 #define SVG2_PROFILE_MAX_CALLS 256
-int svg2_profile_enable(int enable);
+#define SVG2_PROFILE_MAX_SPANS 16384
+enum {
+    SVG2_K_KMEANS_ASSIGN = 0,      /* assign step, Q and K side in one launch (Section 4.1) */
+    SVG2_K_KMEANS_SETTLE = 1,      /* near-ties again in double precision                   */
+    SVG2_K_KMEANS_SORT = 2,        /* counting sort of the labels (3 kernels)               */
+    SVG2_K_KMEANS_SEGSUM_FULL = 3, /* segmented sum over all tokens                         */
+    SVG2_K_KMEANS_SEGSUM_DELTA = 4,/* segmented sum over the tokens whose label changed     */
+    SVG2_K_KMEANS_FINALIZE = 5,    /* means, bf16 copy, norms                               */
+    SVG2_K_PERMUTE_SORT = 6,       /* permutation index vectors of Q and K (3 kernels)      */
+    SVG2_K_PERMUTE_GATHER = 7,     /* permuted copies of Q, K, V                            */
+    SVG2_N_KERNEL_CLASSES = 8
+};
+int svg2_profile_enable(int level);
 int svg2_profile_read(float *stage_ms, int *n_calls);
+int svg2_profile_read_kernels(float *kernel_ms, int *launches);
 
 #ifdef __cplusplus
 }

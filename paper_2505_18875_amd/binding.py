@@ -34,9 +34,11 @@ EXPORTS = (
     "svg2_forward_fp8_workspace_size", "svg2_forward_fp8",
     "svg2_attention_recall_workspace_size", "svg2_attention_recall",
     "svg2_kmeans_pp_init_workspace_size", "svg2_kmeans_pp_init",
-    "svg2_profile_enable", "svg2_profile_read",
+    "svg2_profile_enable", "svg2_profile_read", "svg2_profile_read_kernels",
 )
 STAGES = ("kmeans", "permute", "select", "attn_plan", "attn")
+KERNEL_CLASSES = ("kmeans_assign", "kmeans_settle", "kmeans_sort", "kmeans_segsum_full", "kmeans_segsum_delta",
+                  "kmeans_finalize", "permute_sort", "permute_gather")
 
 
 class Svg2Error(RuntimeError):
@@ -96,6 +98,7 @@ def load_library() -> ctypes.CDLL:
         lib.svg2_kmeans_pp_init.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp, sz, vp]
         lib.svg2_profile_enable.argtypes = [i]
         lib.svg2_profile_read.argtypes = [vp, vp]
+        lib.svg2_profile_read_kernels.argtypes = [vp, vp]
         _lib = lib
     return _lib
 
@@ -387,9 +390,10 @@ def svg2_kmeans_pp_init(X, C, u, *, ws=None):
     return SimpleNamespace(centroids=centroids, picked=picked)
 
 
-def svg2_profile_enable(enable: bool) -> None:
-    """Start / stop recording HIP events around the stages of svg2_forward."""
-    _check(load_library().svg2_profile_enable(int(bool(enable))))
+def svg2_profile_enable(level) -> None:
+    """0 / False: stop; 1 / True: record HIP events around the stages of svg2_forward; 2: also around every
+    kernel launch of k-means and the permutation."""
+    _check(load_library().svg2_profile_enable(int(level)))
 
 
 def svg2_profile_read():
@@ -398,3 +402,12 @@ def svg2_profile_read():
     n = ctypes.c_int(0)
     _check(load_library().svg2_profile_read(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(ctypes.pointer(n), ctypes.c_void_p)))
     return {k: float(v) for k, v in zip(STAGES, ms)}, n.value
+
+
+def svg2_profile_read_kernels():
+    """dict kernel class -> (summed milliseconds, launches) of the spans recorded at profile level 2; clears them."""
+    n = len(KERNEL_CLASSES)
+    ms = (ctypes.c_float * n)()
+    cnt = (ctypes.c_int * n)()
+    _check(load_library().svg2_profile_read_kernels(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(cnt, ctypes.c_void_p)))
+    return {k: (float(m), int(c)) for k, m, c in zip(KERNEL_CLASSES, ms, cnt)}

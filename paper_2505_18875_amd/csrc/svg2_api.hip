@@ -136,12 +136,19 @@ static ForwardLayout forward_layout(void *ws, int dtype, int H, int N, int d, in
     return L;
 }
 
-// ---- optional stage timing (svg2_profile_*) -----------------------------------
+// ---- optional timing (svg2_profile_*) ------------------------------------------
+// Level 1: HIP events around the stages of svg2_forward.  Level 2: additionally an event pair around every kernel
+// launch of the stages that consist of several kernels (k-means, permutation), summed per kernel class.  The events
+// of level 2 sit between kernels that otherwise run back to back, so a level-2 pass is for attributing time, not
+// for timing the layer.
 struct Profiler {
     std::mutex mu;
-    bool on = false;
+    int level = 0;
     int ncalls = 0;
     std::vector<hipEvent_t> ev;          // (SVG2_N_STAGES + 1) events per recorded call
+    std::vector<hipEvent_t> kev;         // pool of event pairs for kernel spans
+    std::vector<int> ktag;               // tag of span i (events 2 i, 2 i + 1 of kev)
+    size_t nspans = 0;
 };
 static Profiler g_prof;
 
@@ -149,7 +156,7 @@ static Profiler g_prof;
 static int profile_begin_call()
 {
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (!g_prof.on || g_prof.ncalls >= SVG2_PROFILE_MAX_CALLS) return -1;
+    if (g_prof.level == 0 || g_prof.ncalls >= SVG2_PROFILE_MAX_CALLS) return -1;
     const size_t need = (size_t)(g_prof.ncalls + 1) * (SVG2_N_STAGES + 1);
     while (g_prof.ev.size() < need) {
         hipEvent_t e;
@@ -162,6 +169,29 @@ static int profile_begin_call()
 static void profile_mark(int base, int k, hipStream_t st)
 {
     if (base >= 0) (void)hipEventRecord(g_prof.ev[base + k], st);
+}
+
+// kernel spans (level 2): span_begin returns a handle for span_end, or -1 when not recording
+int profile_span_begin(int tag, hipStream_t st)
+{
+    if (g_prof.level < 2) return -1;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.nspans >= (size_t)SVG2_PROFILE_MAX_SPANS) return -1;
+    while (g_prof.kev.size() < 2 * (g_prof.nspans + 1)) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return -1;
+        g_prof.kev.push_back(e);
+    }
+    const int i = (int)g_prof.nspans++;
+    if (g_prof.ktag.size() <= (size_t)i) g_prof.ktag.resize(i + 1);
+    g_prof.ktag[i] = tag;
+    (void)hipEventRecord(g_prof.kev[2 * i], st);
+    return i;
+}
+
+void profile_span_end(int handle, hipStream_t st)
+{
+    if (handle >= 0) (void)hipEventRecord(g_prof.kev[2 * handle + 1], st);
 }
 
 }  // namespace svg2
@@ -524,10 +554,10 @@ int svg2_kmeans_pp_init(const void *X, int dtype, int H, int N, int d, int C, co
     return kpp_launch(X, dtype, H, N, d, C, u, centroids, picked, ws, static_cast<hipStream_t>(stream));
 }
 
-int svg2_profile_enable(int enable)
+int svg2_profile_enable(int level)
 {
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.on = enable != 0;
+    g_prof.level = level < 0 ? 0 : (level > 2 ? 2 : level);
     return SVG2_OK;
 }
 
@@ -548,6 +578,23 @@ int svg2_profile_read(float *stage_ms, int *n_calls)
     }
     *n_calls = g_prof.ncalls;
     g_prof.ncalls = 0;
+    return SVG2_OK;
+}
+
+int svg2_profile_read_kernels(float *kernel_ms, int *launches)
+{
+    clear_error();
+    SVG2_REQUIRE(kernel_ms && launches, SVG2_INVALID_ARG, "kernel_ms and launches must be non-null");
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (int k = 0; k < SVG2_N_KERNEL_CLASSES; ++k) { kernel_ms[k] = 0.f; launches[k] = 0; }
+    for (size_t i = 0; i < g_prof.nspans; ++i) {
+        float ms = 0.f;
+        SVG2_HIP_CHECK(hipEventSynchronize(g_prof.kev[2 * i + 1]));
+        SVG2_HIP_CHECK(hipEventElapsedTime(&ms, g_prof.kev[2 * i], g_prof.kev[2 * i + 1]));
+        const int tag = g_prof.ktag[i];
+        if (tag >= 0 && tag < SVG2_N_KERNEL_CLASSES) { kernel_ms[tag] += ms; launches[tag] += 1; }
+    }
+    g_prof.nspans = 0;
     return SVG2_OK;
 }
 

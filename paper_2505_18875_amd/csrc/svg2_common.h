@@ -36,6 +36,18 @@ void clear_error();
 // the first launch of an entry point so that a failure leaves nothing enqueued.
 int set_dynamic_lds(const void *kernel, size_t bytes);
 
+// Kernel-level timing spans (svg2_profile_enable(2)): no-ops unless that level is on.
+int profile_span_begin(int tag, hipStream_t st);
+void profile_span_end(int handle, hipStream_t st);
+struct ProfileSpan {            // RAII: the span covers what is enqueued on `st` during its lifetime
+    int h;
+    hipStream_t st;
+    ProfileSpan(int tag, hipStream_t s) : h(profile_span_begin(tag, s)), st(s) {}
+    ~ProfileSpan() { profile_span_end(h, st); }
+    ProfileSpan(const ProfileSpan &) = delete;
+    ProfileSpan &operator=(const ProfileSpan &) = delete;
+};
+
 // ---- workspace carving -----------------------------------------------------
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 

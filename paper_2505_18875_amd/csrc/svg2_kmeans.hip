@@ -791,7 +791,10 @@ static int kmeans_run(KmArgs a, hipStream_t st)
             hipLaunchKernelGGL(kmeans_zero_kernel, dim3(cdiv(H * iters, 256)), dim3(256), 0, st, a.s[s].objective, H * iters);
         }
     }
-    hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(cmax, H, ns), dim3(D), 0, st, a, 0, 0);
+    {
+        ProfileSpan sp(SVG2_K_KMEANS_FINALIZE, st);
+        hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(cmax, H, ns), dim3(D), 0, st, a, 0, 0);
+    }
     for (int t = 0; t < iters; ++t) {
         // Update step: the first iteration, and every KM_FULL_EVERY-th after that, sums every cluster afresh; the
         // others only move the tokens whose label changed (a quarter in the second iteration, a few per cent from
@@ -810,10 +813,17 @@ static int kmeans_run(KmArgs a, hipStream_t st)
         if (BF16) {
             const dim3 grid(cdiv(cdiv(N, KM_WG_TOKENS), KM_IB), H * ns);
             auto kern = any_obj ? kmeans_assign_bf16_kernel<D, true> : kmeans_assign_bf16_kernel<D, false>;
-            hipLaunchKernelGGL(kern, grid, dim3(64 * KM_NW), kmeans_assign_lds<D>(), st, a, it);
-            hipLaunchKernelGGL((kmeans_settle_kernel<D>), dim3(KM_SETTLE_BLOCKS, H * ns), dim3(256), 0, st, a, it);
+            {
+                ProfileSpan sp(SVG2_K_KMEANS_ASSIGN, st);
+                hipLaunchKernelGGL(kern, grid, dim3(64 * KM_NW), kmeans_assign_lds<D>(), st, a, it);
+            }
+            {
+                ProfileSpan sp(SVG2_K_KMEANS_SETTLE, st);
+                hipLaunchKernelGGL((kmeans_settle_kernel<D>), dim3(KM_SETTLE_BLOCKS, H * ns), dim3(256), 0, st, a, it);
+            }
         } else {
             const dim3 grid(cdiv(N, 128), H);
+            ProfileSpan sp(SVG2_K_KMEANS_ASSIGN, st);
             for (int s = 0; s < ns; ++s) {
                 const float *Xf = reinterpret_cast<const float *>(a.s[s].X);
                 float *obj = a.s[s].objective ? a.s[s].objective + t : nullptr;
@@ -841,13 +851,20 @@ static int kmeans_run(KmArgs a, hipStream_t st)
             sa.s[s].max_pieces = k.max_pieces;
             sa.s[s].seg = KM_SEG;
         }
-        SVG2_TRY(sort_launch(sa, ns, H, N, st));
+        {
+            ProfileSpan sp(SVG2_K_KMEANS_SORT, st);
+            SVG2_TRY(sort_launch(sa, ns, H, N, st));
+        }
         if (full) {
+            ProfileSpan sp(SVG2_K_KMEANS_SEGSUM_FULL, st);
             hipLaunchKernelGGL((kmeans_segsum_kernel<T, D, false>), dim3(cdiv(pmax, 4), H, ns), dim3(256), 0, st, a, it);
-            hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(cmax, H, ns), dim3(D), 0, st, a, 1, it.set);
         } else {
+            ProfileSpan sp(SVG2_K_KMEANS_SEGSUM_DELTA, st);
             hipLaunchKernelGGL((kmeans_segsum_kernel<T, D, true>), dim3(cdiv(pmax, 4), H, 2 * ns), dim3(256), 0, st, a, it);
-            hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(cmax, H, ns), dim3(D), 0, st, a, 2, it.set);
+        }
+        {
+            ProfileSpan sp(SVG2_K_KMEANS_FINALIZE, st);
+            hipLaunchKernelGGL((kmeans_finalize_kernel<BF16>), dim3(cmax, H, ns), dim3(D), 0, st, a, full ? 1 : 2, it.set);
         }
     }
     return SVG2_OK;

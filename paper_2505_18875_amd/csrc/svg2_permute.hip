@@ -264,9 +264,14 @@ int permute_launch(const int32_t *labels, int H, int N, int C, int32_t *offsets,
     a.s[0].offsets = offsets;
     a.s[0].perm = perm;
     a.s[0].inv_perm = inv_perm;
-    const int rc = sort_launch(a, 1, H, N, st);
-    if (rc != SVG2_OK) return rc;
-    if (n_tensors > 0) gather_launch(perm, H, N, n_tensors, src, dst, dtype, d, st);
+    {
+        ProfileSpan sp(SVG2_K_PERMUTE_SORT, st);
+        SVG2_TRY(sort_launch(a, 1, H, N, st));
+    }
+    if (n_tensors > 0) {
+        ProfileSpan sp(SVG2_K_PERMUTE_GATHER, st);
+        gather_launch(perm, H, N, n_tensors, src, dst, dtype, d, st);
+    }
     SVG2_HIP_CHECK(hipGetLastError());
     return SVG2_OK;
 }
@@ -289,9 +294,12 @@ int permute_pair_launch(const int32_t *labels_q, const int32_t *labels_k, int H,
     a.s[1].hist = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + permute_ws_bytes(H, N, Cq));
     a.s[1].offsets = offsets_k;
     a.s[1].perm = perm_k;
-    const int rc = sort_launch(a, 2, H, N, st);
-    if (rc != SVG2_OK) return rc;
+    {
+        ProfileSpan sp(SVG2_K_PERMUTE_SORT, st);
+        SVG2_TRY(sort_launch(a, 2, H, N, st));
+    }
     if (copy) {
+        ProfileSpan sp(SVG2_K_PERMUTE_GATHER, st);
         const void *src_q[1] = {Q};
         void *dst_q[1] = {Qp};
         gather_launch(perm_q, H, N, 1, src_q, dst_q, dtype, d, st);
