@@ -29,7 +29,12 @@
  *     call; outputs and in/out buffers are then undefined.
  *   - dtype is SVG2_F32 or SVG2_BF16 (storage type of Q, K, V, O); d is 64 or
  *     128; 1 <= C <= min(N, SVG2_MAX_CLUSTERS); H >= 1; N >= 1 and
- *     H*N*d < 2^40.  Accumulation is always fp32.
+ *     H*N*d < 2^40.  The attention entry points (svg2_sparse_attn*,
+ *     svg2_forward*, svg2_sparse_attn_fp8) also need one head of K or V to stay
+ *     below 2^31 bytes (N*d*sizeof(element) < 2^31; for svg2_sparse_attn_fp8
+ *     counted at two bytes per element): their kernels address rows by 32-bit
+ *     byte offsets, and a longer head is SVG2_INVALID_ARG.  Attention
+ *     accumulates in fp32.
  *   - Readings of the paper where it is silent: squared Euclidean distance;
  *     one k-means iteration = assign then update; an empty cluster keeps its
  *     centroid; argmin ties go to the lowest cluster index; for bf16 input

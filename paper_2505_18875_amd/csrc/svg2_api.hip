@@ -34,6 +34,16 @@ static int check_common(int dtype, int H, int N, int d)
     return SVG2_OK;
 }
 
+// the attention kernels address the rows of one head's K and V by 32-bit signed byte offsets
+static int check_head_bytes(int dtype, int N, int d)
+{
+    const double bytes = (double)N * (double)d * (dtype == SVG2_F32 ? 4.0 : 2.0);
+    SVG2_REQUIRE(bytes < 2147483648.0, SVG2_INVALID_ARG,
+                 "one head of N = %d rows of d = %d elements has 2^31 bytes or more: the attention kernels cannot address it",
+                 N, d);
+    return SVG2_OK;
+}
+
 // the E4M3 attention kernel exists for bf16 inputs / outputs and 128-byte rows only
 static int check_fp8(int dtype, int d)
 {
@@ -322,6 +332,7 @@ int svg2_sparse_attn(const void *Qp, const void *Kp, const void *Vp, int dtype, 
 {
     clear_error();
     SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_head_bytes(dtype, N, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));
     SVG2_TRY(check_clusters("Ck", Ck, N));
     SVG2_REQUIRE(Qp && Kp && Vp && O && offsets_q && offsets_k && row_ptr && col_idx, SVG2_INVALID_ARG,
@@ -340,6 +351,7 @@ int svg2_sparse_attn_gather_free(const void *Q, const void *K, const void *V, in
 {
     clear_error();
     SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_head_bytes(dtype, N, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));
     SVG2_TRY(check_clusters("Ck", Ck, N));
     SVG2_REQUIRE(Q && K && V && O && offsets_q && offsets_k && row_ptr && col_idx && perm_q && perm_k,
@@ -377,6 +389,7 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
     clear_error();
     const bool gather_free = mode != FWD_PERMUTE;
     SVG2_TRY(check_common(dtype, H, N, d));
+    SVG2_TRY(check_head_bytes(dtype, N, d));
     if (mode == FWD_FP8) SVG2_TRY(check_fp8(dtype, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));
     SVG2_TRY(check_clusters("Ck", Ck, N));
@@ -504,6 +517,7 @@ int svg2_sparse_attn_fp8(const void *Q8, const void *K8, const void *V8, const f
 {
     clear_error();
     SVG2_TRY(check_common(SVG2_BF16, H, N, d));
+    SVG2_TRY(check_head_bytes(SVG2_BF16, N, d));
     SVG2_TRY(check_fp8(SVG2_BF16, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));
     SVG2_TRY(check_clusters("Ck", Ck, N));

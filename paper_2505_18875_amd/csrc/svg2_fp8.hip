@@ -280,26 +280,20 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         if (perm_k) row_ = pkh[row_];                                                      \
         s_rows[((KT) & 1) * ATT_BN + lane] = row_ * RB;                                    \
     }
-// The same in two steps, for the tile loop: the look-up (and, gather-free, the load of the token index) is issued
-// at the top of a tile BEFORE the tile fetches, the result is parked in s_rows at the bottom.  Loads retire in
-// order, so the index has arrived once at most the 2 NPASS fetch instructions issued after it are outstanding
-// (a look-up is only issued when both fetches of that tile top are); waiting for everything would stall on
-// fetches that are meant to stay in flight.  The load is an asm statement so that this wait can be written by hand.
+// The same in two steps, for the tile loop.  ISSUE, once a tile's fetches are on their way: the look-up of a later
+// tile's rows and, gather-free, the load of the token index -- an ordinary load, so the compiler tracks it, with a
+// whole tile of arithmetic to land in.  COMMIT, at the top of the next tile, behind the wait for all outstanding
+// loads and the barrier that open it: the value has landed, and every wavefront has finished reading the half of
+// s_rows that it goes to.
 #define ATT_ROWS_ISSUE(KT)                                                                 \
     if (wave == ((KT) & (NW - 1))) {                                                       \
         const int kk = (KT) * ATT_BN + lane;                                               \
         cur = max(cur, lk_hint);                /* start at the tile's first run (from the plan) */ \
         row_pend = (kk < L) ? run_lookup(s_run, cur, kk) : 0;                              \
-        if (perm_k) {                                                                      \
-            const int32_t *src_ = pkh + row_pend;                                          \
-            asm volatile("global_load_dword %0, %1, off" : "=v"(row_pend) : "v"(src_) : "memory"); \
-        }                                                                                  \
+        if (perm_k) row_pend = pkh[row_pend];                                              \
     }
 #define ATT_ROWS_COMMIT(KT)                                                                \
-    if (wave == ((KT) & (NW - 1))) {                                                       \
-        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(row_pend) : "n"(2 * NPASS));             \
-        s_rows[((KT) & 1) * ATT_BN + lane] = row_pend * RB;                                \
-    }
+    if (wave == ((KT) & (NW - 1))) s_rows[((KT) & 1) * ATT_BN + lane] = row_pend * RB;
 #define ATT_OFFS(KT, OFF)                                                                  \
     _Pragma("unroll") for (int p_ = 0; p_ < NPASS; ++p_)                                   \
         OFF[p_] = (unsigned)s_rows[((KT) & 1) * ATT_BN + (NW * p_ + wave) * RPI + ld_row];
@@ -324,7 +318,16 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
-    if (F8_NSTG == 2 && ntile > 3 && 3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];    // tile 3 is looked up during tile 0
+    if (F8_NSTG == 2) {
+        // tile 3 is looked up here and parked at the top of tile 0; the start of tile 4 is requested for the
+        // look-up at the top of tile 0
+        if (ntile > 3) {
+            if (3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];
+            ATT_ROWS_ISSUE(3)
+        }
+        lk_hint = -1;
+        if (ntile > 4 && 4 < key_tiles && wave == (4 & (NW - 1))) lk_hint = trh[4];
+    }
     if (NSTG > 2) {
         if (ntile > 3) { ATT_ROWS(3) }
         __syncthreads();
@@ -545,12 +548,14 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
         __syncthreads();                                                                   \
         if (HAS_NEXT) {                                                                    \
-            if (kt + NSTG + 1 < ntile) { ATT_ROWS_ISSUE(kt + NSTG + 1) }                   \
+            if (kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }                  \
             if (kt + NSTG - 1 < ntile) { ATT_FETCH(off_nx, Vb, ld_voff, sV + ((BUF + NSTG - 1) % NSTG) * TILE_B) } \
             if (kt + NSTG < ntile) {                                                       \
                 ATT_OFFS(kt + NSTG, off_nx)                                                \
                 ATT_FETCH(off_nx, Kb, ld_koff, sK + BUF * TILE_B)                          \
             }                                                                              \
+            /* rows of tile kt + NSTG + 2, parked at the top of the next tile (its start was requested a tile ago) */ \
+            if (kt + NSTG + 2 < ntile) { ATT_ROWS_ISSUE(kt + NSTG + 2) }                   \
         }                                                                                  \
         if (wave_active) {                                                                 \
             asm volatile("" : "+v"(lt));            /* the registers of the last row sum are free from here on */ \
@@ -570,15 +575,14 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
                 mask_block(s0, 0, L - (kt + 1) * ATT_BN);                                  \
             phase_pv(HN{}, VB{}, s0);                                                      \
         }                                                                                  \
-        if (HAS_NEXT && kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }          \
-        {       /* where the tile that the next tile looks up starts: requested here, used behind the wait at the top */ \
-            const int tn_ = kt + NSTG + 2;                                                 \
+        {       /* where the tile looked up at the top of the next tile starts: requested here */ \
+            const int tn_ = kt + NSTG + 3;                                                 \
             lk_hint = -1;                                                                  \
             if (HAS_NEXT && tn_ < ntile && tn_ < key_tiles && wave == (tn_ & (NW - 1))) lk_hint = trh[tn_]; \
         }                                                                                  \
         ++kt;                                                                              \
     }
-    static_assert(NSTG == 2 || NSTG == 3, "the tile loop is unrolled by the number of buffers");
+    static_assert(NSTG == 2, "the row look-up is parked behind the vmcnt(0) that opens a tile: written for two buffers");
     int kt = 0;
     while (kt < ntile - 1) {
         ATT_TILE(0, true)
