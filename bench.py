@@ -193,14 +193,14 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    svg2.svg2_profile_enable(True)
+    svg2.svg2_profile_enable(1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.warmup, total):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    svg2.svg2_profile_enable(False)
+    svg2.svg2_profile_enable(0)
     stage_ms, n_calls = svg2.svg2_profile_read()
     assert n_calls == args.steps, (n_calls, args.steps)
     ms_per_step = (t1 - t0) * 1e3 / args.steps

@@ -416,21 +416,19 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         ATT_PIN(m_run)
     };
     // The accumulators are expressed under the level m_acc; bring them to m_run.  Called once per tile, right
-    // before the tile is accumulated (both decisions since the last tile are folded into one factor).  The
-    // multiplications are written as in-place instructions: left to the compiler, the rescaled accumulators land
-    // in other registers and the common path (nothing to rescale) pays for it with register copies.
+    // before the tile is accumulated (both decisions since the last tile are folded into one factor).  Ordinary
+    // multiplications: the compiler sees every reader and writer of the accumulators and places the wait states
+    // itself.  The matrix instructions of the previous tile have all completed here (its row sum, the last of
+    // them, was read at the end of that tile).
     auto rescale_if_needed = [&]() {
         if (__any(m_acc != m_run)) {
-            float alpha = __builtin_amdgcn_exp2f(m_acc - m_run);
-            // the exponential comes out of the transcendental unit; the compiler does not look into the asm
-            // statements below when it places the wait state such a result needs before its first use
-            asm volatile("s_nop 3" : "+v"(alpha));
+            const float alpha = __builtin_amdgcn_exp2f(m_acc - m_run);
             m_acc = m_run;
             l_run *= alpha;
 #pragma unroll
             for (int b = 0; b < DVB; ++b)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) asm volatile("v_mul_f32 %0, %1, %0" : "+v"(oacc[b][i]) : "v"(alpha));
+                for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
         }
     };
     // 16-byte half c (0 .. 2 KU - 1) of the K operands of a score block whose first row is at KBYTE

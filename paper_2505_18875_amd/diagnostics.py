@@ -247,20 +247,20 @@ def sequence(args):
                     Qd = (Qd.float() + 0.05 * torch.randn(Qd.shape, generator=g, device="cuda")).to(Qd.dtype)
                     Kd = (Kd.float() + 0.05 * torch.randn(Kd.shape, generator=g, device="cuda")).to(Kd.dtype)
                 iters = w.iters if step == 0 else 2
-                svg2.svg2_profile_enable(True)
+                svg2.svg2_profile_enable(1)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 res = svg2.svg2_forward(Qd, Kd, Vd, cq, ck, p, iters, want_aux=True, out=out, ws=ws)
                 e1.record()
                 torch.cuda.synchronize()
                 st, _ = svg2.svg2_profile_read()
-                svg2.svg2_profile_enable(False)
+                svg2.svg2_profile_enable(0)
                 ms = e0.elapsed_time(e1)
                 if step == 0:
                     t0 = ms
                 else:
                     t_rest += ms / (steps - 1)
-                    t_km += (st["kmeans_q"] + st["kmeans_k"]) / (steps - 1)
+                    t_km += (st["kmeans"]) / (steps - 1)
                     t_at += st["attn"] / (steps - 1)
                     dens += res.aux.density.double().mean().item() / (steps - 1)
             # last step: how far is the 2-iteration warm start from settled labels, and the recall of the selection
