@@ -78,6 +78,28 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     return (bf16_t)(u >> 16);
 }
 
+typedef __attribute__((address_space(3))) unsigned char lds_u8;      // byte in LDS (32-bit address)
+
+// 16 bytes per lane from global memory (base + per-lane byte offset) straight into LDS: lane l lands at dst + 16 l.
+// Written as inline assembly on purpose.  The compiler knows that its own builtin for this instruction writes LDS, cannot
+// tell which part, and therefore waits for ALL outstanding loads (s_waitcnt vmcnt(0)) in front of the next LDS read of
+// any address -- which turned the prefetch of the next tiles into a wait for them.  Here the order is kept by hand: a
+// buffer filled this way is only read after an explicit vmcnt(0) wait and a barrier.  M0 (the LDS address of the
+// instruction) is written inside the statement and named as clobbered, so that the compiler's own M0 set-ups (it keeps M0
+// for itself and merges equal initialisations across blocks) are never carried over one of these statements; clang warns
+// that a clobber of a register it reserves "may not be preserved", which is exactly what the clobber says.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_to_lds_16(const char *base, unsigned byte_off, const unsigned char *dst)
+{
+    const unsigned lds_addr = (unsigned)(size_t)(const lds_u8 *)dst;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(byte_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float *p) { return *p; }

@@ -130,6 +130,15 @@ __device__ __forceinline__ float km_med3(float a, float b, float c)
     return r;
 }
 
+// the values lanes l and l + 32 hold of x: .x = the lower half's, .y = the upper half's, the same in both lanes (one
+// vector instruction; a shuffle across the halves goes through the LDS crossbar and is waited for)
+struct KmHalves { unsigned lo, hi; };
+__device__ __forceinline__ KmHalves km_halves(unsigned x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return {r[0], r[1]};
+}
+
 // double -> bf16, round to nearest even, in ONE rounding: via float unless the float lands exactly on the midpoint
 // of two bf16 values, where the side the double was on decides (and an exact midpoint goes to even).
 __device__ __forceinline__ bf16_t f64_to_bf16(double m)
@@ -232,7 +241,6 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
     extern __shared__ __align__(16) unsigned char s_raw[];
     bf16_t *s_c = reinterpret_cast<bf16_t *>(s_raw);                           // [KM_CMAX][ROW]
     float *s_hcn = reinterpret_cast<float *>(s_raw + (size_t)KM_CMAX * ROW * 2);   // [KM_CMAX]: -||c||^2 / 2
-    __shared__ float s_wmax[KM_NW];
 
     const int side = blockIdx.y % a.nsides, h = blockIdx.y / a.nsides;
     const KmSide S = side ? a.s[1] : a.s[0];
@@ -248,19 +256,8 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
     const int nchunk = (C + KM_CMAX - 1) / KM_CMAX;
     float obj = 0.f;
 
-    // largest ||c||^2 of the head, for the near-tie bound
-    float cmax2;
-    {
-        float m = 0.f;
-        for (int t = tid; t < C; t += 64 * KM_NW) m = fmaxf(m, -2.f * hcnh[t]);
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        if (lane == 0) s_wmax[wave] = m;
-        __syncthreads();
-        m = s_wmax[0];
-#pragma unroll
-        for (int w = 1; w < KM_NW; ++w) m = fmaxf(m, s_wmax[w]);
-        cmax2 = m;
-    }
+    float cmax2 = 0.f;          // largest ||c||^2 of the head (over the chunks so far), for the near-tie bound
+    static_assert(64 * KM_NW == KM_CMAX, "one -||c||^2/2 per thread");
 
 #define KM_FENCE __builtin_amdgcn_sched_barrier(0);
 #define KM_PIN(X)
@@ -269,44 +266,75 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
         const int cc = min(KM_CMAX, C - c0), ccp = (cc + 31) & ~31;
         const bool last_chunk = chunk + 1 == nchunk;
         __syncthreads();
-        // stage the chunk (rows past the last centroid are zero and can never win); a thread requests all its
-        // pieces before it stores the first, so the block waits for one round trip to memory, not sixteen
-        {
-            constexpr int PER = KM_CMAX * (D / 8) / (64 * KM_NW);
-            uint4 v[PER];
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid + i * 64 * KM_NW, r = e / (D / 8), part = e % (D / 8);
-                v[i] = make_uint4(0, 0, 0, 0);
-                if (r < cc) v[i] = reinterpret_cast<const uint4 *>(cbh + (size_t)(c0 + r) * D)[part];
-            }
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int e = tid + i * 64 * KM_NW, r = e / (D / 8), part = e % (D / 8);
-                if (r < ccp) *reinterpret_cast<uint4 *>(&s_c[r * ROW + part * 8]) = v[i];
-            }
-        }
-        for (int t = tid; t < ccp; t += 64 * KM_NW) s_hcn[t] = (t < cc) ? hcnh[c0 + t] : KM_PAD_HCN;
-        __syncthreads();
-
-        // Token blocks of the item, two register buffers: the tokens of block b + 1 are requested
-        // from global memory before block b is computed.
-        // tokens as the B operand: lane (col, half) holds elements 16 s + 8 half .. + 8 of token `col`
+        // Token blocks of the item, two register buffers.  Tokens as the B operand: lane (col, half) holds elements
+        // 16 s + 8 half .. + 8 of token `col`.  The KM_TB * KS loads of a block come in four parts; while block b is
+        // computed, the parts of block b + 1 are requested one by one between its steps (all eight wavefronts of
+        // the workgroup asking for a whole block at the same moment queue up in front of the texture unit, and
+        // each of them waits for the queue).
         bf16x8 xb[2][KM_TB][KS];
-        auto load_x = [&](auto buf_tag, int b) {
-            constexpr int BUF = decltype(buf_tag)::value;
+        constexpr int NLD = KM_TB * KS, LPP = NLD / 4;
+        auto load_part = [&](auto buf_tag, int b, auto part_tag) {
+            constexpr int BUF = decltype(buf_tag)::value, PART = decltype(part_tag)::value;
             const int tok0 = (blk0 + b) * KM_WG_TOKENS + wave * (KM_TB * 32);
 #pragma unroll
-            for (int tb = 0; tb < KM_TB; ++tb) {
+            for (int i = PART * LPP; i < (PART + 1) * LPP; ++i) {
+                const int tb = i / KS, s = i % KS;
                 const int n = min(N - 1, tok0 + tb * 32 + col);
-                const uint4 *src = reinterpret_cast<const uint4 *>(Xh + (size_t)n * D + 8 * half);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    const uint4 v = src[2 * s];
-                    __builtin_memcpy(&xb[BUF][tb][s], &v, 16);
-                }
+                const uint4 v = reinterpret_cast<const uint4 *>(Xh + (size_t)n * D + 8 * half)[2 * s];
+                __builtin_memcpy(&xb[BUF][tb][s], &v, 16);
             }
         };
+        auto load_x = [&](auto buf_tag, int b) {
+            load_part(buf_tag, b, std::integral_constant<int, 0>{});
+            load_part(buf_tag, b, std::integral_constant<int, 1>{});
+            load_part(buf_tag, b, std::integral_constant<int, 2>{});
+            load_part(buf_tag, b, std::integral_constant<int, 3>{});
+        };
+        // stage the chunk (rows past the last centroid are zero and can never win).  A thread requests all its
+        // pieces before it stores the first, so the block waits for one round trip to memory, not sixteen;
+        // no branches (a row past the end re-reads the last one and is zeroed in registers), and every workgroup
+        // starts at another row, so that the workgroups of a head that run side by side do not ask the same L2
+        // channel for the same line at the same moment.
+        {
+            constexpr int PER = KM_CMAX * (D / 8) / (64 * KM_NW), HALF = PER;
+            static_assert((KM_CMAX & (KM_CMAX - 1)) == 0, "row rotation wraps with a mask");
+            const int rot = (int)(blockIdx.x * 37u) & (KM_CMAX - 1);
+            // the addresses are formed here, in every chunk: formed once in front of the chunk loop (where the
+            // compiler would move them) they would sit in scratch memory while the token blocks are computed
+            int tid_o = tid;
+            asm volatile("" : "+v"(tid_o));
+#pragma unroll
+            for (int i0 = 0; i0 < PER; i0 += HALF) {
+                uint4 v[HALF];
+#pragma unroll
+                for (int i = 0; i < HALF; ++i) {
+                    const int e = tid_o + (i0 + i) * 64 * KM_NW, r = ((e / (D / 8)) + rot) & (KM_CMAX - 1);
+                    v[i] = reinterpret_cast<const uint4 *>(cbh + (size_t)(c0 + min(r, cc - 1)) * D)[e % (D / 8)];
+                }
+                // in the same round trip: this thread's -||c||^2/2 and the wavefront's first block of tokens
+                const float hv = hcnh[c0 + min(tid_o, cc - 1)];
+                load_x(std::integral_constant<int, 0>{}, 0);
+#pragma unroll
+                for (int i = 0; i < HALF; ++i) {
+                    const int e = tid_o + (i0 + i) * 64 * KM_NW, r = ((e / (D / 8)) + rot) & (KM_CMAX - 1);
+                    if (r >= cc) v[i] = make_uint4(0, 0, 0, 0);
+                    *reinterpret_cast<uint4 *>(&s_c[r * ROW + (e % (D / 8)) * 8]) = v[i];
+                }
+                s_hcn[tid] = tid < cc ? hv : KM_PAD_HCN;
+            }
+        }
+        __syncthreads();
+        {
+            float m = cmax2;
+#pragma unroll
+            for (int k = 0; k < KM_CMAX / 64; ++k) {
+                const int t = lane + 64 * k;
+                m = fmaxf(m, t < cc ? -2.f * s_hcn[t] : 0.f);
+            }
+            for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+            cmax2 = m;
+        }
+
         // Accumulator i of a lane is centroid 8 (i/4) + 4 half + i%4 of the row block; its key is the accumulator
         // with i in its 4 lowest mantissa bits, compared as a float.  best = largest key seen, second = runner-up,
         // bbase = first centroid of the row block (and lane half) the best came from.
@@ -322,6 +350,12 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 bbase[tb] = 0;
             }
             const int nrb = ccp / 32;
+            // steps after which the four parts of the next block are requested: spread over the first half of a
+            // long block (the loads then have the second half to land in), all at once when the block is short
+            const int pstep = nrb >= 8 ? nrb / 8 : 0;
+            // everything this wavefront has requested so far -- the tokens of this block -- has to be there; said
+            // here, in front of the loop, the compiler places no wait inside it
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             bf16x8 am[KS];
             f32x16 cinit;
             auto fetch_c = [&](int rb) {
@@ -415,6 +449,13 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
 #pragma unroll
                     for (int s = 0; s < KS; ++s) fetch_a(rb + 1, s);
                 }
+                {
+                    using NB = std::integral_constant<int, BUF ^ 1>;
+                    if (rb == 0) load_part(NB{}, b + 1, std::integral_constant<int, 0>{});
+                    if (rb == pstep) load_part(NB{}, b + 1, std::integral_constant<int, 1>{});
+                    if (rb == 2 * pstep) load_part(NB{}, b + 1, std::integral_constant<int, 2>{});
+                    if (rb == 3 * pstep) load_part(NB{}, b + 1, std::integral_constant<int, 3>{});
+                }
                 KM_FENCE
                 const int rbase = c0 + rb * 32 + 4 * half;
 #pragma unroll
@@ -429,12 +470,13 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
 #pragma unroll
             for (int tb = 0; tb < KM_TB; ++tb) {
                 const unsigned kb = __float_as_uint(best[tb]);
-                int cidx = bbase[tb] + (int)(((kb & 12u) << 1) | (kb & 3u));
+                const int cown = bbase[tb] + (int)(((kb & 12u) << 1) | (kb & 3u));
                 // the two lane halves of a token hold disjoint centroids
-                const float ob = __shfl_xor(best[tb], 32), os = __shfl_xor(second[tb], 32);
-                const int oi = __shfl_xor(cidx, 32);
-                float T = km_max(best[tb], ob), U = km_max3(km_min(best[tb], ob), second[tb], os);
-                if (ob > best[tb]) cidx = oi;
+                const KmHalves hb = km_halves(kb), hs = km_halves(__float_as_uint(second[tb])),
+                               hi = km_halves((unsigned)cown);
+                const float b0 = __uint_as_float(hb.lo), b1 = __uint_as_float(hb.hi);
+                float T = km_max(b0, b1), U = km_max3(km_min(b0, b1), __uint_as_float(hs.lo), __uint_as_float(hs.hi));
+                int cidx = (b1 > b0) ? (int)hi.hi : (int)hi.lo;
                 const int n = tok0 + tb * 32 + col;
                 if (chunk > 0) {
                     // best and runner-up over the earlier chunks (read here, behind the loop: a load in front of
@@ -457,7 +499,10 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                             const bf16x2_t p2 = {xb[BUF][tb][s][2 * e], xb[BUF][tb][s][2 * e + 1]};
                             x2 = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, x2, false);
                         }
-                    x2 += __shfl_xor(x2, 32);
+                    {
+                        const KmHalves hx = km_halves(__float_as_uint(x2));
+                        x2 = __uint_as_float(hx.lo) + __uint_as_float(hx.hi);
+                    }
                     // runner-up within the error of this contraction: the token is settled in double precision
                     // (a tie, including an exact one, always is)
                     const float tau = KM_TIE_KEY * fabsf(T) + KM_TIE_ACC * (0.5f * x2 + cmax2);
@@ -478,17 +523,14 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
         };
         // Blocks of this item that hold tokens (wavefront-uniform).  The tokens of the block after the one being
         // computed are ALWAYS requested (past the end of the item the addresses are clamped and the values unused):
-        // with a conditional prefetch the compiler has to place waits that are also right for the path without
-        // it, i.e. it waits for the youngest loads -- the prefetch itself -- in the first step of every block.
+        // with a conditional prefetch the compiler has to place waits that are also right for the path without it.
         const int nblk = min(KM_IB, (N - blk0 * KM_WG_TOKENS + KM_WG_TOKENS - 1) / KM_WG_TOKENS);
-        load_x(std::integral_constant<int, 0>{}, 0);
 #pragma unroll 1
         for (int b = 0; b < nblk; b += 2) {
-            load_x(std::integral_constant<int, 1>{}, b + 1);
             compute(std::integral_constant<int, 0>{}, b);
-            load_x(std::integral_constant<int, 0>{}, b + 2);
             if (b + 1 < nblk) compute(std::integral_constant<int, 1>{}, b + 1);
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // the last, unused request: the registers are reused from here on
     }
 #undef KM_FENCE
 #undef KM_PIN
