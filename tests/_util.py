@@ -75,6 +75,64 @@ def upload_heads(w, heads):
     return Q, K, V, cq, ck
 
 
+def bisector_case(d, C, N=24000, n_tie=2000):
+    """Centroids and tokens for the near-tie test below: (X [N,d], cent [C,d], number of exact ties built)."""
+    r = np.random.default_rng(4100 + d + C)
+    cent = wl.round_to_bf16((3.0 * r.standard_normal((C, d))).astype(np.float32))
+    # a quarter of the centroids get a twin that differs in ONE coordinate by two units in the last place, so that
+    # the mid-point of the pair is a bf16 number: tokens there are exactly tied (the lower index has to win)
+    order = r.permutation(C)
+    twins = []
+    for i in range(C // 4):
+        j, t = sorted((int(order[2 * i]), int(order[2 * i + 1])))
+        k = int(r.integers(0, d))
+        bits = int(wl.bf16_bits(cent[j:j + 1, k])[0])
+        tw = wl.bf16_bits_to_f32(np.array([bits + 2], dtype=np.uint16))[0]
+        m = np.float32(0.5 * (float(cent[j, k]) + float(tw)))
+        if np.isfinite(tw) and wl.round_to_bf16(np.array([m]))[0] == m and m != cent[j, k] and m != tw:
+            cent[t] = cent[j]
+            cent[t, k] = tw
+            twins.append((j, t, k, m))
+    a = r.integers(0, C, size=N)
+    b = (a + 1 + r.integers(0, C - 1, size=N)) % C
+    mid = 0.5 * (cent[a].astype(np.float64) + cent[b].astype(np.float64))
+    delta = (cent[a] - cent[b]).astype(np.float64)
+    X = wl.round_to_bf16(mid.astype(np.float32))
+    # The rounding of X alone puts a token hundreds of rounding errors away from the hyperplane.  Walk it back: move
+    # single coordinates to their neighbouring bf16 values until (x - mid).delta, the difference of the two scores,
+    # is as close as it gets to a target drawn log-uniformly between 1e-6 and 1e-1 on either side.
+    target = np.exp(r.uniform(np.log(1e-6), np.log(1e-1), size=N)) * r.choice([-1.0, 1.0], size=N)
+    rows = np.arange(N)
+    for _ in range(48):
+        g = ((X.astype(np.float64) - mid) * delta).sum(axis=1)
+        bits = wl.bf16_bits(X).astype(np.int64)
+        best_err, best_k, best_v = np.abs(g - target), np.full(N, -1), np.zeros(N, dtype=np.float32)
+        for db in (1, -1):
+            nb = wl.bf16_bits_to_f32(np.clip(bits + db, 0, 0xFFFF).astype(np.uint16))
+            ok = np.isfinite(nb) & ((bits & 0x7FFF) + db >= 0)
+            err = np.abs(g[:, None] + (nb.astype(np.float64) - X) * delta - target[:, None])
+            err[~ok] = np.inf
+            k = err.argmin(axis=1)
+            better = err[rows, k] < best_err
+            best_err = np.where(better, err[rows, k], best_err)
+            best_k = np.where(better, k, best_k)
+            best_v = np.where(better, nb[rows, k], best_v)
+        move = best_k >= 0
+        if not move.any():
+            break
+        X[rows[move], best_k[move]] = best_v[move]
+    # exact ties: the pair's mid-point in the coordinate where the twins differ, the centroid's own value plus some
+    # noise (the same for both, so the tie stays exact) in eight others
+    for i in range(n_tie if twins else 0):
+        j, t, k, m = twins[int(r.integers(0, len(twins)))]
+        x = cent[j].copy()
+        other = r.choice(np.delete(np.arange(d), k), size=8, replace=False)
+        x[other] = wl.round_to_bf16((x[other] + 0.5 * r.standard_normal(8)).astype(np.float32))
+        x[k] = m
+        X[i] = x
+    return X, cent, (n_tie if twins else 0)
+
+
 def csr_rows(row_ptr, col_idx):
     return [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in range(len(row_ptr) - 1)]
 

@@ -165,6 +165,30 @@ def test_kmeans_tie_goes_to_lowest_index_and_empty_cluster_keeps_centroid(oracle
     assert res.labels[0] == 1
 
 
+def test_kmeans_labels_on_near_ties_and_exact_ties_follow_exact_arithmetic(oracle):
+    """The input of the GPU's near-tie test (tokens next to, and exactly on, the hyperplane between two centroids):
+    the oracle's labels are the argmin of the squared distances in EXACT arithmetic -- Python integers on the bf16
+    values scaled to integers -- with the lower index on a tie.  A float64 shortcut in the oracle that lost the
+    last bits of a near-tie, or a tie rule that went the other way, fails here."""
+    from _util import bisector_case
+    X, cent, n_tie = bisector_case(64, 24, N=1500, n_tie=300)
+    assert n_tie == 300
+    res = oracle.kmeans(X, cent, 1, True)
+    # bf16 values are integers times 2^-133 at the finest; these inputs are O(1..10) with 8-bit mantissas, so 2^40
+    # scales every value to an exact integer that Python's integers then square and sum without rounding
+    Xi = [[int(v) for v in row] for row in np.round(X.astype(np.float64) * 2.0 ** 40)]
+    Ci = [[int(v) for v in row] for row in np.round(cent.astype(np.float64) * 2.0 ** 40)]
+    assert np.array_equal(np.array(Xi, dtype=np.float64) * 2.0 ** -40, X.astype(np.float64))
+    assert np.array_equal(np.array(Ci, dtype=np.float64) * 2.0 ** -40, cent.astype(np.float64))
+    ties = 0
+    for n, x in enumerate(Xi):
+        dist = [sum((a - b) * (a - b) for a, b in zip(x, c)) for c in Ci]
+        best = min(dist)
+        ties += dist.count(best) > 1
+        assert res.labels[n] == dist.index(best), (n, res.labels[n], dist.index(best))
+    assert ties >= 250
+
+
 def test_kmeans_assign_sees_bf16_rounded_centroids(oracle):
     r = _rng(7)
     X = r.standard_normal((400, 16)).astype(np.float32)
