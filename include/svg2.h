@@ -39,7 +39,12 @@
  *     one k-means iteration = assign then update; an empty cluster keeps its
  *     centroid; argmin ties go to the lowest cluster index; for bf16 input
  *     the assign step uses the centroids rounded to bf16 (returned centroids
- *     stay fp32 means); tokens keep their original order inside a cluster;
+ *     stay fp32 means: the cluster sums are formed in double precision and
+ *     rounded once) and its labels are those of exact arithmetic on these
+ *     operands (a token whose two best candidates are closer than the rounding
+ *     error of the fp32 contraction is re-decided in double precision); for
+ *     fp32 input the labels are those of fp32 arithmetic; tokens keep their
+ *     original order inside a cluster;
  *     top-p keeps the cluster whose mass crosses p; equal P' goes to the lower
  *     index; empty key clusters are never selected; softmax is renormalised
  *     over the selected keys.
