@@ -28,7 +28,8 @@
  *     touched.  SVG2_HIP_ERROR can also come from a launch in the middle of a
  *     call; outputs and in/out buffers are then undefined.
  *   - dtype is SVG2_F32 or SVG2_BF16 (storage type of Q, K, V, O); d is 64 or
- *     128; 1 <= C <= min(N, SVG2_MAX_CLUSTERS); H >= 1; N >= 1 and
+ *     128; 1 <= C <= min(N, SVG2_MAX_CLUSTERS); 1 <= H <= 65535 (svg2_forward*:
+ *     H <= 32767); N >= 1 and
  *     H*N*d < 2^40.  The attention entry points (svg2_sparse_attn*,
  *     svg2_forward*, svg2_sparse_attn_fp8) also need one head of K or V to stay
  *     below 2^31 bytes (N*d*sizeof(element) < 2^31; for svg2_sparse_attn_fp8

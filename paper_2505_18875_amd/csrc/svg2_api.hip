@@ -389,6 +389,8 @@ static int forward_impl(const void *Q, const void *K, const void *V, int dtype, 
     clear_error();
     const bool gather_free = mode != FWD_PERMUTE;
     SVG2_TRY(check_common(dtype, H, N, d));
+    // k-means runs the Q and the K side of every head in the same launches: 2 H entries in one grid dimension
+    SVG2_REQUIRE(H <= 32767, SVG2_INVALID_ARG, "H = %d exceeds 32767, the limit of the svg2_forward calls", H);
     SVG2_TRY(check_head_bytes(dtype, N, d));
     if (mode == FWD_FP8) SVG2_TRY(check_fp8(dtype, d));
     SVG2_TRY(check_clusters("Cq", Cq, N));

@@ -74,6 +74,8 @@ def test_workspace_queries_and_validation_run_on_the_host(lib):
     assert rc == 1 and b"alias" in lib.svg2_last_error()
     rc = lib.svg2_forward(one, one, one, 1, 1, 16, 128, 1, 1, 0.9, 0, one, one, vp(512), None, one, 1 << 30, None)
     assert rc == 1 and b"iters" in lib.svg2_last_error()
+    rc = lib.svg2_forward(one, one, one, 1, 40000, 64, 128, 1, 1, 0.9, 1, one, one, vp(512), None, one, 1 << 30, None)
+    assert rc == 1 and b"32767" in lib.svg2_last_error()
     # a head of 2^31 bytes or more cannot be addressed by the attention kernels' 32-bit row offsets
     rc = lib.svg2_sparse_attn(one, one, one, 0, 1, 1 << 22, 128, 1, 1, one, one, one, one, None, 0.0, vp(512), None,
                               one, 1 << 20, None)

@@ -422,6 +422,26 @@ def test_attention_many_heads_work_order_fallback(svg2, oracle):
         np.testing.assert_allclose(to_np(res.lse[h]), lse_ref, rtol=1e-3, atol=2e-3)
 
 
+def test_forward_largest_number_of_heads(svg2, oracle):
+    # 32,767 heads (the most the layer call takes: k-means puts both sides of every head into one grid dimension) of
+    # a very short sequence; three heads are checked against the oracle stage by stage
+    from types import SimpleNamespace
+    H, N, d, Cq, Ck, iters, p = 32767, 48, 64, 3, 5, 2, 0.9
+    w = SimpleNamespace(dtype="bf16", Cq=Cq, Ck=Ck, N=N, d=d)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    Q, K, V = (torch.randn((H, N, d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+               for _ in range(3))
+    cq, ck = Q[:, :Cq].float().contiguous(), K[:, 7:7 + Ck].float().contiguous()
+    cq0, ck0 = cq.clone(), ck.clone()
+    res = svg2.svg2_forward(Q, K, V, cq, ck, p, iters, want_aux=True)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(res.O.float()).all())
+    assert torch.equal(res.aux.counts_k.sum(dim=1), torch.full((H,), N, device="cuda"))
+    for h in (0, 20011, H - 1):
+        check_layer_head(svg2, oracle, w, to_np(Q[h]), to_np(K[h]), to_np(V[h]), to_np(cq0[h]), to_np(ck0[h]), iters, p,
+                         res.aux, h, res.O[h], cq[h], ck[h], Q[h:h + 1], K[h:h + 1], labels_exact=True)
+
+
 def test_forward_tiny(svg2, oracle):
     _check_forward(oracle, svg2, wl.WORKLOADS["tiny"], [0])
 
