@@ -450,6 +450,14 @@ def test_forward_small_two_heads(svg2, oracle):
     _check_forward(oracle, svg2, wl.WORKLOADS["small"], [3, 17], sample_rows=768)
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 128)])
+def test_forward_other_storage_type_and_head_dimension(svg2, oracle, dtype, d):
+    # the two combinations no benchmark configuration uses: bf16 tensors with head dimension 64 (matrix-core kernels
+    # instantiated for 64) and fp32 tensors with head dimension 128 (the plain-arithmetic kernels), every row
+    w = wl.replace(wl.WORKLOADS["small"], grid=(4, 20, 24), d=d, dtype=dtype, Cq=24, Ck=70, iters=4)
+    _check_forward(oracle, svg2, w, [2, 9])
+
+
 def test_forward_top_p_one_is_dense_attention(svg2, oracle):
     # Section 4.1: with every block selected the permuted computation equals dense attention
     w = wl.replace(wl.WORKLOADS["small"], grid=(4, 16, 16), Cq=12, Ck=40, iters=2, top_p=1.0)
