@@ -82,6 +82,7 @@ def _check_select(oracle, res, cq, ck, counts_q, counts_k, p, H):
 @pytest.mark.parametrize("H,Cq,Ck,d,p", [
     (2, 16, 32, 64, 0.9), (3, 100, 500, 128, 0.9), (2, 100, 500, 128, 0.5),
     (1, 7, 1000, 128, 0.95), (1, 5, 4096, 64, 0.8), (2, 33, 77, 128, 1.0), (1, 1, 1, 64, 0.3),
+    (2, 20, 50, 128, 1e-6),          # p so small that every row keeps exactly its first cluster
 ])
 def test_select_topp_csr(svg2, oracle, H, Cq, Ck, d, p):
     r = np.random.default_rng(200 + Cq + Ck)
