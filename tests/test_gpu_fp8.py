@@ -146,6 +146,40 @@ def test_sparse_attn_fp8_ragged_and_empty_clusters(svg2, oracle):
         assert rows.size and np.all(O[rows] == 0.0) and np.all(np.isneginf(lse[rows]))
 
 
+def test_sparse_attn_fp8_scores_that_climb_between_tiles(svg2, oracle):
+    """Keys ordered so that every query's scores grow along the key sequence by more per 32-key block than the
+    head-room the kernel leaves above its reference level: the level moves in nearly every block (within a tile
+    too, which makes the kernel redo the tile's first block), the accumulators are rescaled by factors down to
+    zero, and one key ends up with all the weight."""
+    r = np.random.default_rng(29)
+    N, d = 1600, 128
+    u = r.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    Q = wl.round_to_bf16((4.0 * u[None] + 0.3 * r.standard_normal((N, d))).astype(np.float32) * 10.0)
+    ramp = np.linspace(-12.0, 12.0, N).astype(np.float32)
+    K = wl.round_to_bf16((ramp[:, None] * u[None] + 0.3 * r.standard_normal((N, d))).astype(np.float32) * 10.0)
+    V = wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32))
+    lq = (np.arange(N) % 4).astype(np.int32)
+    lk = (np.arange(N) // 200).astype(np.int32)
+    sel = [np.arange(8), np.array([0, 1, 2]), np.array([7]), np.array([3, 5])]
+    pq, pk = oracle.permute(lq, 4), oracle.permute(lk, 8)
+    row_ptr = np.concatenate([[0], np.cumsum([len(x) for x in sel])]).astype(np.int32)
+    col = np.zeros(4 * 8, dtype=np.int32)
+    cat = np.concatenate(sel).astype(np.int32)
+    col[: cat.size] = cat
+    (Q8, sq), (K8, sk), (V8, sv) = _quantise_all(svg2, to_dev(Q[None], "bf16"), to_dev(K[None], "bf16"),
+                                                 to_dev(V[None], "bf16"))
+    res = svg2.svg2_sparse_attn_fp8(Q8, K8, V8, sq, sk, sv, to_dev(pq.offsets[None]), to_dev(pk.offsets[None]),
+                                    to_dev(row_ptr[None]), to_dev(col[None]), to_dev(pq.perm[None]),
+                                    to_dev(pk.perm[None]), want_lse=True)
+    torch.cuda.synchronize()
+    O, lse = to_np(res.O[0]).astype(np.float64), to_np(res.lse[0]).astype(np.float64)
+    # rows with a handful of keys that matter: the errors of a row are not independent, so no sigma-based check;
+    # lse is compared at the size of the scores (hundreds), where 1e-3 relative is what fp32 scores allow
+    _check_head(oracle, O, lse, Q, K, V, d, pq.perm, pk.perm, pq.offsets, pk.offsets, row_ptr, col, statistical=False,
+                lse_mean=0.07)
+
+
 def test_sparse_attn_fp8_thousands_of_short_key_clusters(svg2, oracle):
     """Key clusters of one or two rows: a 64-key tile crosses dozens of runs of the virtual key sequence, and the row
     look-up of a tile starts from the run the plan recorded for it."""

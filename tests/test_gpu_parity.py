@@ -318,6 +318,31 @@ def test_attention_random_blocks_with_ragged_and_empty_clusters(svg2, oracle, dt
         assert rows.size and np.all(O[rows] == 0.0)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_scores_that_climb_by_hundreds_between_tiles(svg2, oracle, dtype):
+    """Keys sorted so that the scores of every query grow along the key sequence by far more than the head-room
+    the kernels leave before they move the reference level of the running softmax: the level moves in almost
+    every block, the accumulators are rescaled by factors that underflow to zero, and at the end one key holds
+    all the weight.  Logits reach +-400 and grow by ~17 per block of 32 keys, so nothing here survives without the
+    subtraction of the maximum."""
+    r = np.random.default_rng(23)
+    N, d = 1600, 128
+    u = r.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    Q = wl.round_to_bf16((4.0 * u[None] + 0.3 * r.standard_normal((N, d))).astype(np.float32) * 10.0)
+    ramp = np.linspace(-12.0, 12.0, N).astype(np.float32)
+    K = wl.round_to_bf16((ramp[:, None] * u[None] + 0.3 * r.standard_normal((N, d))).astype(np.float32) * 10.0)
+    V = wl.round_to_bf16(r.standard_normal((N, d)).astype(np.float32))
+    lq = (np.arange(N) % 4).astype(np.int32)
+    lk = (np.arange(N) // 200).astype(np.int32)            # 8 key clusters in ramp order
+    sel = [np.arange(8), np.array([0, 1, 2]), np.array([7]), np.array([3, 5])]
+    # fp32: a score of magnitude 500 formed from 128 fp32 products carries an absolute error of a few 1e-4 (2^-24 x 500
+    # per rounding), which is the relative error of the probabilities of two keys that compete for a row: the max-abs
+    # bar of 1e-4 set for scores of ordinary size becomes 1e-3 here, the mean bar stays
+    _attn_case(oracle, svg2, Q, K, V, lq, lk, sel, dtype, few_keys=True,
+               tol=(2e-2, 1e-3) if dtype == "bf16" else (1e-3, 1e-5))
+
+
 @pytest.mark.parametrize("d", [128, 64])
 def test_attention_tile_loop_edges_random_small_shapes(svg2, oracle, d):
     """The matrix-core kernel's tile loop has a schedule with look-ahead (K two tiles ahead, V one, the row look-up
