@@ -195,6 +195,29 @@ def test_kmeans_tokens_on_and_next_to_bisectors_get_the_oracles_labels(svg2, ora
     np.testing.assert_array_equal(to_np(res.counts[0]), ref.counts)
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_kmeans_duplicate_centroids_tie_everywhere(svg2, oracle, d):
+    # two pairs of identical initial centroids: every token that is nearest to one of them is exactly tied with its
+    # twin (thousands of near-ties for the double-precision pass at once); the lower index takes them all, the
+    # twin stays empty and keeps its centroid
+    r = np.random.default_rng(61 + d)
+    N, C, iters = 6000, 12, 3
+    X = wl.round_to_bf16((r.standard_normal((1, N, d)) + 2.0 * r.standard_normal((1, 1, d))).astype(np.float32))
+    init = X[:, r.choice(N, C, replace=False)].copy()
+    init[0, 7] = init[0, 2]
+    init[0, 11] = init[0, 5]
+    one = svg2.svg2_kmeans(to_dev(X, "bf16"), to_dev(init), 1)
+    torch.cuda.synchronize()
+    _check_kmeans(oracle, one, X, init, 1, True, 1, C)
+    assert int(one.counts[0, 7]) == 0 and int(one.counts[0, 11]) == 0
+    assert int(one.counts[0, 2]) > 0 and int(one.counts[0, 5]) > 0
+    np.testing.assert_array_equal(to_np(one.centroids[0, 7]), init[0, 7])
+    # further iterations: the twins stay where they were (on a token each, which they then win back)
+    res = svg2.svg2_kmeans(to_dev(X, "bf16"), to_dev(init), iters)
+    torch.cuda.synchronize()
+    _check_kmeans(oracle, res, X, init, iters, True, 1, C)
+
+
 def test_kmeans_empty_cluster_keeps_centroid_and_warm_start(svg2, oracle):
     r = np.random.default_rng(7)
     X = wl.round_to_bf16(r.standard_normal((1, 2000, 128)).astype(np.float32))
