@@ -167,7 +167,9 @@ def test_kmeans_small_bf16(svg2, oracle, iters):
 @pytest.mark.parametrize("dtype,d,N,C", [("bf16", 64, 1000, 33), ("f32", 128, 777, 50), ("bf16", 128, 513, 513),
                                          ("bf16", 128, 700, 1), ("f32", 64, 300, 300),
                                          # more centroids than the LDS holds at once, several token blocks per item
-                                         ("bf16", 128, 5000, 1000), ("bf16", 64, 4500, 1100)])
+                                         ("bf16", 128, 5000, 1000), ("bf16", 64, 4500, 1100),
+                                         # the smallest inputs there are
+                                         ("bf16", 128, 1, 1), ("bf16", 64, 5, 5), ("f32", 64, 2, 1), ("f32", 128, 1, 1)])
 def test_kmeans_ragged_shapes(svg2, oracle, dtype, d, N, C):
     r = np.random.default_rng(300 + N)
     X = r.standard_normal((2, N, d)).astype(np.float32) + 2.0 * r.standard_normal((2, 1, d)).astype(np.float32)
@@ -489,6 +491,25 @@ def test_forward_largest_number_of_heads(svg2, oracle):
     for h in (0, 20011, H - 1):
         check_layer_head(svg2, oracle, w, to_np(Q[h]), to_np(K[h]), to_np(V[h]), to_np(cq0[h]), to_np(ck0[h]), iters, p,
                          res.aux, h, res.O[h], cq[h], ck[h], Q[h:h + 1], K[h:h + 1], labels_exact=True)
+
+
+@pytest.mark.parametrize("N,Cq,Ck", [(1, 1, 1), (2, 2, 1), (70, 3, 70)])
+def test_forward_shortest_sequences(svg2, oracle, N, Cq, Ck):
+    # the whole layer on one token, two tokens, and with every key its own cluster
+    from types import SimpleNamespace
+    H, d, iters, p = 3, 128, 2, 0.9
+    w = SimpleNamespace(dtype="bf16", Cq=Cq, Ck=Ck, N=N, d=d)
+    g = torch.Generator(device="cuda").manual_seed(100 + N)
+    Q, K, V = (torch.randn((H, N, d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+               for _ in range(3))
+    cq, ck = Q[:, :Cq].float().contiguous(), K[:, :Ck].float().contiguous()
+    cq0, ck0 = cq.clone(), ck.clone()
+    res = svg2.svg2_forward(Q, K, V, cq, ck, p, iters, want_aux=True)
+    torch.cuda.synchronize()
+    for h in range(H):
+        check_layer_head(svg2, oracle, w, to_np(Q[h]), to_np(K[h]), to_np(V[h]), to_np(cq0[h]), to_np(ck0[h]), iters, p,
+                         res.aux, h, res.O[h], cq[h], ck[h], Q[h:h + 1], K[h:h + 1], labels_exact=True,
+                         tol=(2e-2, 1e-3 + 2.0 ** -9))     # O(1) outputs: bf16 storage of O on top of the mean bar
 
 
 def test_forward_tiny(svg2, oracle):
