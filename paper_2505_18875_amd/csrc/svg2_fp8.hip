@@ -173,8 +173,9 @@ __device__ __forceinline__ long lds_read_tr8(const lds_u8 *p)
     return r;
 }
 
-static constexpr int F8_NSTG = 2;           // K and V tile buffers in LDS (each): 2 or 3.  Measured on the Wan-like layer
-                                            // (8-head probe, ms sparse / dense): 2 buffers 5.08 / 14.9, 3 buffers 5.30 / 15.6
+static constexpr int F8_NSTG = 2;           // K and V tile buffers in LDS (each).  A third one (tiles requested a tile
+                                            // earlier) was measured slower on the Wan-like layer (8-head probe, ms sparse /
+                                            // dense: 5.30 / 15.6 against 5.08 / 14.9); the tile loop is written for two
 static constexpr float F8_HEADROOM = 8.0f;  // a score may exceed the reference level by 2^8 before it moves
 static constexpr float F8_LEVEL = 6.0f;     // the reference level is put 2^6 below the block maximum
 
@@ -314,28 +315,17 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
     if (ntile > 1) {
         ATT_OFFS(1, off_nx)
         ATT_FETCH(off_nx, Kb, ld_koff, sK + TILE_B)
-        if (NSTG > 2) { ATT_FETCH(off_nx, Vb, ld_voff, sV + TILE_B) }
     }
     __syncthreads();                            // everyone has read the rows of tiles 0 and 1
     if (ntile > 2) { ATT_ROWS(2) }
-    if (F8_NSTG == 2) {
-        // tile 3 is looked up here and parked at the top of tile 0; the start of tile 4 is requested for the
-        // look-up at the top of tile 0
-        if (ntile > 3) {
-            if (3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];
-            ATT_ROWS_ISSUE(3)
-        }
-        lk_hint = -1;
-        if (ntile > 4 && 4 < key_tiles && wave == (4 & (NW - 1))) lk_hint = trh[4];
+    // tile 3 is looked up here and parked at the top of tile 0; the start of tile 4 is requested for the look-up at
+    // the top of tile 0
+    if (ntile > 3) {
+        if (3 < key_tiles && wave == (3 & (NW - 1))) lk_hint = trh[3];
+        ATT_ROWS_ISSUE(3)
     }
-    if (NSTG > 2) {
-        if (ntile > 3) { ATT_ROWS(3) }
-        __syncthreads();
-        if (ntile > 2) {
-            ATT_OFFS(2, off_nx)
-            ATT_FETCH(off_nx, Kb, ld_koff, sK + 2 * TILE_B)
-        }
-    }
+    lk_hint = -1;
+    if (ntile > 4 && 4 < key_tiles && wave == (4 & (NW - 1))) lk_hint = trh[4];
     // off_nx stays live: the rows of tile NSTG - 1, whose V is requested at the top of tile 0
 
     // per-lane LDS read addresses (buffer 0): the two 16-byte halves of K operand u, V^T operand of column block b
@@ -542,8 +532,7 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
 #define ATT_TILE(BUF, HAS_NEXT)                                                            \
     {                                                                                      \
         /* the fetches issued NSTG - 1 tiles ago (V of this tile, K of the next) must have landed */ \
-        if (NSTG > 2 && kt + NSTG - 1 < ntile) __builtin_amdgcn_s_waitcnt(0x0F70 | ((NSTG - 2) * 2 * NPASS)); \
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                                           \
+        __builtin_amdgcn_s_waitcnt(0x0F70);         /* vmcnt(0) */                         \
         __syncthreads();                                                                   \
         if (HAS_NEXT) {                                                                    \
             if (kt + NSTG + 1 < ntile) { ATT_ROWS_COMMIT(kt + NSTG + 1) }                  \
@@ -586,16 +575,11 @@ __global__ __launch_bounds__(64 * ATT_NW, 8 / ATT_NW) void attn_fp8_kernel(
         ATT_TILE(0, true)
         if (kt >= ntile - 1) break;
         ATT_TILE(1, true)
-        if constexpr (NSTG == 3) {
-            if (kt >= ntile - 1) break;
-            ATT_TILE((NSTG - 1), true)
-        }
     }
     if (ntile > 0) {
         const int bl = kt % NSTG;
         if (bl == 0) ATT_TILE(0, false)
-        else if (bl == 1) ATT_TILE(1, false)
-        else if constexpr (NSTG == 3) ATT_TILE((NSTG - 1), false)
+        else ATT_TILE(1, false)
     }
 #undef ATT_TILE
 #undef ATT_FENCE
