@@ -26,6 +26,7 @@
 // For bf16 input the assign step sees the centroids rounded to bf16 (both in x.c and in ||c||^2); the
 // centroids handed back stay fp32 means.
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "svg2_common.h"
@@ -40,7 +41,6 @@ static constexpr int KM_CMAX = 512;    // centroids resident in LDS at a time (b
 static constexpr int KM_NW = 8;        // wavefronts per workgroup (bf16 kernel)
 static constexpr int KM_TB = 2;        // 32-token blocks per wavefront (bf16 kernel)
 static constexpr int KM_WG_TOKENS = KM_NW * KM_TB * 32;
-static constexpr int KM_IB = 8;        // token blocks per work item (bf16 kernel)
 static constexpr int KM_UB = 4;        // load instructions in flight per wavefront in the segmented sum
 static constexpr int KM_SEG = 256;     // rows per piece of the segmented sum
 static constexpr int KM_FULL_EVERY = 16; // iterations between updates that sum every cluster afresh (the others move the changed tokens)
@@ -216,11 +216,15 @@ __global__ void kmeans_finalize_kernel(KmArgs a, int mode, int set)
 }
 
 // ---------------------------------------------------------------- assign, bf16 MFMA
-// grid (items, H * sides), block 64 * KM_NW, one workgroup per CU.  A work item is KM_IB blocks of KM_WG_TOKENS
-// tokens of one head and side; the head's centroids (up to KM_CMAX at a time) stay in LDS for the whole item.
+// grid (one workgroup per CU), block 64 * KM_NW.  The blocks of KM_WG_TOKENS tokens of all heads of a side form one
+// sequence; workgroup w takes the w-th of gridDim.x equal parts of it, on both sides: even workgroups first on the
+// second side (the K tokens of a layer: many centroids, bound by the matrix cores) and then on the first (the Q
+// tokens: few centroids, waiting for memory), odd workgroups the other way round, so that the two kinds of work
+// share the chip at any time.  A part is cut at head boundaries into spans; the head's centroids (up to KM_CMAX
+// at a time) are staged in LDS once per span and stay there for all its blocks.  (One workgroup per 4096 tokens,
+// placed by the hardware, was measured 6 % slower on a layer: six stagings and six workgroup starts per CU.)
 // With more than KM_CMAX centroids the running best and runner-up of a token go through `best` / `second`
-// between chunks.  Sides alternate along the grid so that the memory-bound side (few centroids) and the
-// matrix-bound side (many) are in flight together.
+// between chunks.
 //
 // A wavefront owns two blocks of 32 tokens.  Per 32-centroid row block it issues the 2 KS matrix instructions of
 // both, then reduces their accumulators to (best, runner-up) with max3 / med3 trees while the other wavefront of
@@ -242,25 +246,39 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
     bf16_t *s_c = reinterpret_cast<bf16_t *>(s_raw);                           // [KM_CMAX][ROW]
     float *s_hcn = reinterpret_cast<float *>(s_raw + (size_t)KM_CMAX * ROW * 2);   // [KM_CMAX]: -||c||^2 / 2
 
-    const int side = blockIdx.y % a.nsides, h = blockIdx.y / a.nsides;
-    const KmSide S = side ? a.s[1] : a.s[0];
-    int32_t *labels = side ? it.lab[1] : it.lab[0];
-    const int N = a.N, C = S.C;
+    const int N = a.N;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
-    const int blk0 = blockIdx.x * KM_IB;
-    if (blk0 * KM_WG_TOKENS >= N) return;
-    const bf16_t *Xh = reinterpret_cast<const bf16_t *>(S.X) + (size_t)h * N * D;
-    const bf16_t *cbh = S.cb + (size_t)h * C * D;
-    const float *hcnh = S.hcn + (size_t)h * C;
-    const int nchunk = (C + KM_CMAX - 1) / KM_CMAX;
-    float obj = 0.f;
-
-    float cmax2 = 0.f;          // largest ||c||^2 of the head (over the chunks so far), for the near-tie bound
+    const int nbh = (N + KM_WG_TOKENS - 1) / KM_WG_TOKENS;          // token blocks of a head
+    const int nb_all = a.H * nbh;                                   // H N d < 2^40: below 2^25
     static_assert(64 * KM_NW == KM_CMAX, "one -||c||^2/2 per thread");
 
 #define KM_FENCE __builtin_amdgcn_sched_barrier(0);
 #define KM_PIN(X)
+    // this workgroup's part of the block sequence, the same for both sides
+    const int part_q = nb_all / (int)gridDim.x, part_r = nb_all % (int)gridDim.x;
+    const int part_lo = (int)blockIdx.x * part_q + min((int)blockIdx.x, part_r);
+    const int part_hi = part_lo + part_q + ((int)blockIdx.x < part_r ? 1 : 0);
+#pragma unroll 1
+    for (int sd = 0; sd < a.nsides; ++sd) {
+    // odd workgroups start with the first side, even ones with the second: while one half of the CUs is on the Q
+    // tokens of a layer (few centroids, waits for memory) the other is on the K tokens (many, matrix cores)
+    const int side = (blockIdx.x & 1) ? sd : a.nsides - 1 - sd;
+    const KmSide S = side ? a.s[1] : a.s[0];
+    int32_t *labels = side ? it.lab[1] : it.lab[0];
+    const int C = S.C;
+    const int nchunk = (C + KM_CMAX - 1) / KM_CMAX;
+#pragma unroll 1
+    for (int sp = part_lo; sp < part_hi;) {
+    // span: blocks blk0 .. blk0 + nblk of head h
+    const int h = sp / nbh, blk0 = sp - h * nbh;
+    const int nblk = min(nbh - blk0, part_hi - sp);
+    sp += nblk;
+    const bf16_t *Xh = reinterpret_cast<const bf16_t *>(S.X) + (size_t)h * N * D;
+    const bf16_t *cbh = S.cb + (size_t)h * C * D;
+    const float *hcnh = S.hcn + (size_t)h * C;
+    float obj = 0.f;
+    float cmax2 = 0.f;          // largest ||c||^2 of the head (over the chunks so far), for the near-tie bound
     for (int chunk = 0; chunk < nchunk; ++chunk) {
         const int c0 = chunk * KM_CMAX;
         const int cc = min(KM_CMAX, C - c0), ccp = (cc + 31) & ~31;
@@ -349,6 +367,10 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 second[tb] = -INFINITY;
                 bbase[tb] = 0;
             }
+            // The two wavefronts of a SIMD (w and w + 4) get different priorities: with equal ones they fall into
+            // step, both in their matrix instructions and then both in their reductions, and each unit idles
+            // while the other works.
+            if (wave & 4) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
             const int nrb = ccp / 32;
             // steps after which the four parts of the next block are requested: spread over the first half of a
             // long block (the loads then have the second half to land in), all at once when the block is short
@@ -521,10 +543,9 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 }
             }
         };
-        // Blocks of this item that hold tokens (wavefront-uniform).  The tokens of the block after the one being
-        // computed are ALWAYS requested (past the end of the item the addresses are clamped and the values unused):
-        // with a conditional prefetch the compiler has to place waits that are also right for the path without it.
-        const int nblk = min(KM_IB, (N - blk0 * KM_WG_TOKENS + KM_WG_TOKENS - 1) / KM_WG_TOKENS);
+        // The tokens of the block after the one being computed are ALWAYS requested (past the end of the span the
+        // addresses are clamped and the values unused): with a conditional prefetch the compiler has to place waits
+        // that are also right for the path without it.
 #pragma unroll 1
         for (int b = 0; b < nblk; b += 2) {
             compute(std::integral_constant<int, 0>{}, b);
@@ -532,12 +553,14 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // the last, unused request: the registers are reused from here on
     }
-#undef KM_FENCE
-#undef KM_PIN
     if (OBJ && S.objective) {
         for (int o = 32; o > 0; o >>= 1) obj += __shfl_xor(obj, o);
         if (lane == 0) atomicAdd(S.objective + (size_t)h * a.iters + it.t, obj);
     }
+    }   // spans
+    }   // sides
+#undef KM_FENCE
+#undef KM_PIN
 }
 
 // ---------------------------------------------------------------- settle near-ties, bf16 input
@@ -819,10 +842,28 @@ int kmeans_prepare(int dtype, int d)
     return SVG2_OK;
 }
 
+// number of compute units of the current device (the bf16 assign kernel runs one workgroup on each)
+static int device_cu_count(int *ncu)
+{
+    static std::atomic<int> known[64];
+    int dev = -1;
+    SVG2_HIP_CHECK(hipGetDevice(&dev));
+    int n = (dev >= 0 && dev < 64) ? known[dev].load() : 0;
+    if (n <= 0) {
+        SVG2_HIP_CHECK(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        SVG2_REQUIRE(n > 0, SVG2_HIP_ERROR, "device %d reports %d compute units", dev, n);
+        if (dev >= 0 && dev < 64) known[dev].store(n);
+    }
+    *ncu = n;
+    return SVG2_OK;
+}
+
 template <typename T, int D, bool BF16>
 static int kmeans_run(KmArgs a, hipStream_t st)
 {
     const int H = a.H, N = a.N, iters = a.iters, ns = a.nsides;
+    int ncu = 0;
+    if (BF16) SVG2_TRY(device_cu_count(&ncu));
     int cmax = 0, pmax = 0;
     bool any_obj = false;
     for (int s = 0; s < ns; ++s) {
@@ -853,7 +894,8 @@ static int kmeans_run(KmArgs a, hipStream_t st)
             it.lab_prev[s] = alt ? a.s[s].labels : a.s[s].labels_alt;
         }
         if (BF16) {
-            const dim3 grid(cdiv(cdiv(N, KM_WG_TOKENS), KM_IB), H * ns);
+            const long long nb_all = (long long)H * cdiv(N, KM_WG_TOKENS);
+            const dim3 grid((unsigned)std::min<long long>(ncu, nb_all));
             auto kern = any_obj ? kmeans_assign_bf16_kernel<D, true> : kmeans_assign_bf16_kernel<D, false>;
             {
                 ProfileSpan sp(SVG2_K_KMEANS_ASSIGN, st);
