@@ -243,8 +243,11 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
     constexpr int ROW = D + 8;              // LDS row stride in elements (16 bytes of padding)
     constexpr int NCH = 8;                  // chunks of a top-2 reduction
     extern __shared__ __align__(16) unsigned char s_raw[];
-    bf16_t *s_c = reinterpret_cast<bf16_t *>(s_raw);                           // [KM_CMAX][ROW]
-    float *s_hcn = reinterpret_cast<float *>(s_raw + (size_t)KM_CMAX * ROW * 2);   // [KM_CMAX]: -||c||^2 / 2
+    // -||c||^2 / 2 first: its reads then have offsets below 64 KB, which fit the instruction, and cost no address
+    // arithmetic in the step loop
+    float *s_hcn = reinterpret_cast<float *>(s_raw);                               // [KM_CMAX]: -||c||^2 / 2
+    bf16_t *s_c = reinterpret_cast<bf16_t *>(s_raw + KM_CMAX * sizeof(float));     // [KM_CMAX][ROW]
+    __shared__ int s_next;                  // next group of a span that no wavefront has taken yet
 
     const int N = a.N;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -284,16 +287,20 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
         const int cc = min(KM_CMAX, C - c0), ccp = (cc + 31) & ~31;
         const bool last_chunk = chunk + 1 == nchunk;
         __syncthreads();
-        // Token blocks of the item, two register buffers.  Tokens as the B operand: lane (col, half) holds elements
-        // 16 s + 8 half .. + 8 of token `col`.  The KM_TB * KS loads of a block come in four parts; while block b is
-        // computed, the parts of block b + 1 are requested one by one between its steps (all eight wavefronts of
-        // the workgroup asking for a whole block at the same moment queue up in front of the texture unit, and
-        // each of them waits for the queue).
+        // The span is handed out in groups of KM_TB * 32 tokens: wavefront w starts with group w and then takes
+        // the next one nobody has taken (the two wavefronts of a SIMD do not run at the same speed, see the
+        // priorities below; with a fixed share the fast ones would wait for the slow ones at the end of the span).
+        if (tid == 0) s_next = KM_NW;               // read after the barrier behind the staging
+        // Two register buffers.  Tokens as the B operand: lane (col, half) holds elements 16 s + 8 half .. + 8 of
+        // token `col`.  The KM_TB * KS loads of a group come in four parts; while a group is computed, the parts of
+        // the wavefront's next one are requested one by one between its steps (all eight wavefronts of the
+        // workgroup asking for a whole group at the same moment queue up in front of the texture unit, and each
+        // of them waits for the queue).
         bf16x8 xb[2][KM_TB][KS];
         constexpr int NLD = KM_TB * KS, LPP = NLD / 4;
-        auto load_part = [&](auto buf_tag, int b, auto part_tag) {
+        auto load_part = [&](auto buf_tag, int g, auto part_tag) {
             constexpr int BUF = decltype(buf_tag)::value, PART = decltype(part_tag)::value;
-            const int tok0 = (blk0 + b) * KM_WG_TOKENS + wave * (KM_TB * 32);
+            const int tok0 = blk0 * KM_WG_TOKENS + g * (KM_TB * 32);
 #pragma unroll
             for (int i = PART * LPP; i < (PART + 1) * LPP; ++i) {
                 const int tb = i / KS, s = i % KS;
@@ -302,11 +309,11 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 __builtin_memcpy(&xb[BUF][tb][s], &v, 16);
             }
         };
-        auto load_x = [&](auto buf_tag, int b) {
-            load_part(buf_tag, b, std::integral_constant<int, 0>{});
-            load_part(buf_tag, b, std::integral_constant<int, 1>{});
-            load_part(buf_tag, b, std::integral_constant<int, 2>{});
-            load_part(buf_tag, b, std::integral_constant<int, 3>{});
+        auto load_x = [&](auto buf_tag, int g) {
+            load_part(buf_tag, g, std::integral_constant<int, 0>{});
+            load_part(buf_tag, g, std::integral_constant<int, 1>{});
+            load_part(buf_tag, g, std::integral_constant<int, 2>{});
+            load_part(buf_tag, g, std::integral_constant<int, 3>{});
         };
         // stage the chunk (rows past the last centroid are zero and can never win).  A thread requests all its
         // pieces before it stores the first, so the block waits for one round trip to memory, not sixteen;
@@ -331,7 +338,7 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 }
                 // in the same round trip: this thread's -||c||^2/2 and the wavefront's first block of tokens
                 const float hv = hcnh[c0 + min(tid_o, cc - 1)];
-                load_x(std::integral_constant<int, 0>{}, 0);
+                load_x(std::integral_constant<int, 0>{}, wave);
 #pragma unroll
                 for (int i = 0; i < HALF; ++i) {
                     const int e = tid_o + (i0 + i) * 64 * KM_NW, r = ((e / (D / 8)) + rot) & (KM_CMAX - 1);
@@ -353,12 +360,41 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
             cmax2 = m;
         }
 
+        // What a block of tokens writes (label; running pair or the near-tie list) is held back until the tokens of
+        // the next block have been waited for: that wait is for ALL outstanding memory operations, and behind the
+        // stores it would last a round trip to memory although the tokens arrived long ago.
+        int pend_n[KM_TB], pend_c[KM_TB];
+        float pend_T[KM_TB], pend_U[KM_TB];
+        bool pend_f[KM_TB], pend = false;
+        auto flush = [&]() {
+            if (!pend) return;
+            pend = false;
+#pragma unroll
+            for (int tb = 0; tb < KM_TB; ++tb) {
+                const int n = pend_n[tb];
+                if (half == 0 && n < N) {
+                    labels[(size_t)h * N + n] = pend_c[tb];
+                    if (!last_chunk) {
+                        S.best[(size_t)h * N + n] = pend_T[tb];
+                        S.second[(size_t)h * N + n] = pend_U[tb];
+                    } else if (pend_f[tb]) {
+                        const int pos = atomicAdd(&S.flag_cnt[h], 1);
+                        S.flag_list[(size_t)h * N + pos] = n;
+                    }
+                }
+            }
+        };
         // Accumulator i of a lane is centroid 8 (i/4) + 4 half + i%4 of the row block; its key is the accumulator
         // with i in its 4 lowest mantissa bits, compared as a float.  best = largest key seen, second = runner-up,
-        // bbase = first centroid of the row block (and lane half) the best came from.
-        auto compute = [&](auto buf_tag, int b) {
+        // bbase = first centroid of the row block the best came from (the same number in every lane: the select
+        // then takes it from a scalar register).
+        auto compute = [&](auto buf_tag, int g) -> int {
             constexpr int BUF = decltype(buf_tag)::value;
-            const int tok0 = (blk0 + b) * KM_WG_TOKENS + wave * (KM_TB * 32);
+            // the group after this one (taken here, so that the answer is there when the first step wants it)
+            int g_next = 0;
+            if (lane == 0) g_next = atomicAdd(&s_next, 1);
+            g_next = __builtin_amdgcn_readfirstlane(g_next);
+            const int tok0 = blk0 * KM_WG_TOKENS + g * (KM_TB * 32);
             float best[KM_TB], second[KM_TB];
             int bbase[KM_TB];
 #pragma unroll
@@ -378,6 +414,7 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
             // everything this wavefront has requested so far -- the tokens of this block -- has to be there; said
             // here, in front of the loop, the compiler places no wait inside it
             __builtin_amdgcn_s_waitcnt(0x0F70);
+            flush();
             bf16x8 am[KS];
             f32x16 cinit;
             auto fetch_c = [&](int rb) {
@@ -473,13 +510,13 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                 }
                 {
                     using NB = std::integral_constant<int, BUF ^ 1>;
-                    if (rb == 0) load_part(NB{}, b + 1, std::integral_constant<int, 0>{});
-                    if (rb == pstep) load_part(NB{}, b + 1, std::integral_constant<int, 1>{});
-                    if (rb == 2 * pstep) load_part(NB{}, b + 1, std::integral_constant<int, 2>{});
-                    if (rb == 3 * pstep) load_part(NB{}, b + 1, std::integral_constant<int, 3>{});
+                    if (rb == 0) load_part(NB{}, g_next, std::integral_constant<int, 0>{});
+                    if (rb == pstep) load_part(NB{}, g_next, std::integral_constant<int, 1>{});
+                    if (rb == 2 * pstep) load_part(NB{}, g_next, std::integral_constant<int, 2>{});
+                    if (rb == 3 * pstep) load_part(NB{}, g_next, std::integral_constant<int, 3>{});
                 }
                 KM_FENCE
-                const int rbase = c0 + rb * 32 + 4 * half;
+                const int rbase = c0 + rb * 32;
 #pragma unroll
                 for (int q = 0; q < KM_TB; ++q) {
                     KmTop2 r;
@@ -492,7 +529,7 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
 #pragma unroll
             for (int tb = 0; tb < KM_TB; ++tb) {
                 const unsigned kb = __float_as_uint(best[tb]);
-                const int cown = bbase[tb] + (int)(((kb & 12u) << 1) | (kb & 3u));
+                const int cown = bbase[tb] + 4 * half + (int)(((kb & 12u) << 1) | (kb & 3u));
                 // the two lane halves of a token hold disjoint centroids
                 const KmHalves hb = km_halves(kb), hs = km_halves(__float_as_uint(second[tb])),
                                hi = km_halves((unsigned)cown);
@@ -531,27 +568,22 @@ __global__ __launch_bounds__(64 * KM_NW, 1) void kmeans_assign_bf16_kernel(KmArg
                     flagged = half == 0 && n < N && !(T - U > tau);
                     if (OBJ && S.objective && half == 0 && n < N) obj += x2 - 2.f * T;
                 }
-                if (half == 0 && n < N) {
-                    labels[(size_t)h * N + n] = cidx;
-                    if (!last_chunk) {
-                        S.best[(size_t)h * N + n] = T;
-                        S.second[(size_t)h * N + n] = U;
-                    } else if (flagged) {
-                        const int pos = atomicAdd(&S.flag_cnt[h], 1);
-                        S.flag_list[(size_t)h * N + pos] = n;
-                    }
-                }
+                pend_n[tb] = n; pend_c[tb] = cidx; pend_T[tb] = T; pend_U[tb] = U; pend_f[tb] = flagged;
             }
+            pend = true;
+            return g_next;
         };
-        // The tokens of the block after the one being computed are ALWAYS requested (past the end of the span the
+        // The tokens of the group after the one being computed are ALWAYS requested (past the end of the span the
         // addresses are clamped and the values unused): with a conditional prefetch the compiler has to place waits
         // that are also right for the path without it.
+        const int ng = nblk * KM_NW;
 #pragma unroll 1
-        for (int b = 0; b < nblk; b += 2) {
-            compute(std::integral_constant<int, 0>{}, b);
-            if (b + 1 < nblk) compute(std::integral_constant<int, 1>{}, b + 1);
+        for (int g = wave; g < ng;) {
+            g = compute(std::integral_constant<int, 0>{}, g);
+            if (g < ng) g = compute(std::integral_constant<int, 1>{}, g);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);     // the last, unused request: the registers are reused from here on
+        flush();
     }
     if (OBJ && S.objective) {
         for (int o = 32; o > 0; o >>= 1) obj += __shfl_xor(obj, o);
