@@ -626,6 +626,10 @@ __global__ __launch_bounds__(256) void kmeans_settle_kernel(KmArgs a, KmIter it)
         double best = INFINITY;
         int bj = 0x7FFFFFFF;
         for (int j0 = 64 * wave; j0 < C; j0 += 256) {
+            // the token is read from LDS as it is used: kept in registers across this loop it takes 2 D of them, one
+            // workgroup then fills a CU, and most workgroups of a launch find nothing to do -- how fast they come
+            // and go decides how long the launch takes (55 us per launch on the Wan-like layer that way, 26 us so)
+            asm volatile("" ::: "memory");
             const int j = min(j0 + lane, C - 1);
             uint4 w4[D / 8];
 #pragma unroll
