@@ -36,7 +36,7 @@ HBM_PEAK_GBPS = 8000.0                  # MI355X HBM3E peak
 # layer at top-p 0.9, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 1 GiB copy
 # in the same runs): profiles/wan_like_attention_hbm_traffic.md.  A constant from that profile, not measured by
 # this script (counters need the profiler); other workloads report null.
-ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 17320346.2 + 1034588.3) * 1024.0}
+ATTN_TRAFFIC_BYTES = {("wan_like", 0.9): (2.0 * 17221511.7 + 1030321.2) * 1024.0}
 ATTN_TRAFFIC_SOURCE = ("fabric-side bytes (L2 misses, FETCH_SIZE / WRITE_SIZE), part of which the Infinity Cache serves; "
                        "constant from profiles/wan_like_attention_hbm_traffic.md, not measured in this run")
 
