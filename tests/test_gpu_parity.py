@@ -181,6 +181,30 @@ def test_kmeans_ragged_shapes(svg2, oracle, dtype, d, N, C):
     _check_kmeans(oracle, res, X, init, 3, dtype == "bf16", 2, C)
 
 
+@pytest.mark.parametrize("H,N,C", [(300, 700, 40), (77, 1300, 520)])
+def test_kmeans_many_heads_a_workgroups_share_crosses_head_boundaries(svg2, oracle, H, N, C):
+    # The bf16 assign kernel gives every CU an equal share of the 512-token blocks of ALL heads: with a few blocks per
+    # head and hundreds of heads a share starts in the middle of one head, ends in the middle of another and covers
+    # whole heads in between (each with its own centroids to stage), and the last block of every head is ragged.
+    # 520 centroids: two passes over the tokens of every span.  A sample of heads against the oracle, the rest by
+    # what must hold for any head.
+    r = np.random.default_rng(4000 + H)
+    X = wl.round_to_bf16(r.standard_normal((H, N, 128)).astype(np.float32) + 1.5 * r.standard_normal((H, 1, 128)).astype(np.float32))
+    init = np.stack([X[h][np.sort(r.choice(N, C, replace=False))] for h in range(H)]).astype(np.float32)
+    res = svg2.svg2_kmeans(to_dev(X, "bf16"), to_dev(init), 3)
+    torch.cuda.synchronize()
+    labels, counts = to_np(res.labels), to_np(res.counts)
+    assert labels.min() >= 0 and labels.max() < C
+    for h in range(H):
+        np.testing.assert_array_equal(counts[h], np.bincount(labels[h], minlength=C))
+    for h in sorted(set([0, 1, 2, H // 3, H // 2, H - 2, H - 1]) | set(int(x) for x in r.choice(H, 5, replace=False))):
+        ref = oracle.kmeans(X[h], init[h], 3, True)
+        np.testing.assert_array_equal(labels[h], ref.labels, err_msg="head %d" % h)
+        np.testing.assert_array_equal(counts[h], ref.counts)
+        err = np.abs(to_np(res.centroids[h]) - ref.centroids).max(axis=1) / np.maximum(np.abs(ref.centroids).max(axis=1), 1e-6)
+        assert err.max() < 1e-3, "head %d: centroid error %.3g" % (h, err.max())
+
+
 @pytest.mark.parametrize("d,C", [(128, 64), (128, 500), (64, 96), (128, 1000)])
 def test_kmeans_tokens_on_and_next_to_bisectors_get_the_oracles_labels(svg2, oracle, d, C):
     """Every token sits next to the hyperplane half-way between two centroids, at distances from it that range
