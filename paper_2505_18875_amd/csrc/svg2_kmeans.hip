@@ -221,13 +221,13 @@ __global__ void kmeans_finalize_kernel(KmArgs a, int mode, int set)
 // second side (the K tokens of a layer: many centroids, bound by the matrix cores) and then on the first (the Q
 // tokens: few centroids, waiting for memory), odd workgroups the other way round, so that the two kinds of work
 // share the chip at any time.  A part is cut at head boundaries into spans; the head's centroids (up to KM_CMAX
-// at a time) are staged in LDS once per span and stay there for all its blocks.  (One workgroup per 4096 tokens,
-// placed by the hardware, was measured 6 % slower on a layer: six stagings and six workgroup starts per CU.)
-// With more than KM_CMAX centroids the running best and runner-up of a token go through `best` / `second`
+// at a time) are staged in LDS once per span and stay there for all its blocks.  (One workgroup per 4096 tokens of
+// one side, placed by the hardware, was measured 15 % slower on a layer: the launch then took the sum of the times
+// the two sides take alone.)  With more than KM_CMAX centroids the running best and runner-up of a token go through `best` / `second`
 // between chunks.
 //
-// A wavefront owns two blocks of 32 tokens.  Per 32-centroid row block it issues the 2 KS matrix instructions of
-// both, then reduces their accumulators to (best, runner-up) with max3 / med3 trees while the other wavefront of
+// A wavefront takes 64 tokens at a time, as two blocks of 32.  Per 32-centroid row block it issues the 2 KS matrix
+// instructions of both, then reduces their accumulators to (best, runner-up) with max3 / med3 trees while the other wavefront of
 // the SIMD has the matrix cores.
 //
 // Near-ties (see KM_TIE_*) are listed for kmeans_settle_kernel.
