@@ -222,8 +222,8 @@ __global__ void kmeans_finalize_kernel(KmArgs a, int mode, int set)
 // tokens: few centroids, waiting for memory), odd workgroups the other way round, so that the two kinds of work
 // share the chip at any time.  A part is cut at head boundaries into spans; the head's centroids (up to KM_CMAX
 // at a time) are staged in LDS once per span and stay there for all its blocks.  (One workgroup per 4096 tokens of
-// one side, placed by the hardware, was measured 15 % slower on a layer: the launch then took the sum of the times
-// the two sides take alone.)  With more than KM_CMAX centroids the running best and runner-up of a token go through `best` / `second`
+// one side, placed by the hardware, took 0.59 instead of 0.50 ms per launch on a layer of 40 heads of 75,600 tokens
+// with 100 and 500 centroids: the sum of the times the two sides take alone.)  With more than KM_CMAX centroids the running best and runner-up of a token go through `best` / `second`
 // between chunks.
 //
 // A wavefront takes 64 tokens at a time, as two blocks of 32.  Per 32-centroid row block it issues the 2 KS matrix
